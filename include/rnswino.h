@@ -1,0 +1,154 @@
+/*
+ * rnswino -- exact INT8 2-D convolution by Winograd minimal filtering inside a
+ * residue number system, for AMD MI355X (gfx950).  C ABI.
+ *
+ * Method: "Efficient Residue Number System Based Winograd Convolution"
+ * (arXiv 2007.12216).  A quantised layer g (*) x between an (R x R x C x K)
+ * signed-int8 weight tensor and a (B x W x H x C) signed-int8 input
+ * (section 6, first paragraph) is computed with F(M x M, R x R) over
+ * RNS(m_0 .. m_{n-1}) (section 5, eq. "fast_algorithm_rns"; section 6, eqs.
+ * "direct_sum_winograd" / "direct_sum_2" / "gemm"), and the result is
+ * converted back from the residues by mixed-radix conversion (section 3).
+ * The result is the exact integer convolution (abstract; section 9).
+ *
+ * In this header the paper's M, R, N = M+R-1 are spelled m, r, t; N, C, K, H, W
+ * are the tensor dimensions.  Tensors are NCHW / KCrr, contiguous, in DEVICE
+ * memory unless a parameter says "host".
+ *
+ * Ownership: the caller owns every device buffer (x, w, U, workspace, y).  A
+ * plan owns only its own small constant tables (host and device).  None of
+ * rnswino_filter_transform / rnswino_conv2d / rnswino_requant_pool allocates,
+ * frees or synchronises: they enqueue kernels on `stream` (a hipStream_t
+ * passed as void*, NULL = the default stream) and return.  Calls that share a
+ * workspace must be ordered by the caller (same stream or events).
+ *
+ * Errors: every int-returning function returns RNSWINO_OK (0) or a negative
+ * code; nothing throws, aborts or prints.
+ */
+#ifndef RNSWINO_H
+#define RNSWINO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RNSWINO_OK = 0,
+  RNSWINO_E_INVALID = -1,              /* null pointer, non-positive size, t > 16, m < 1, output empty      */
+  RNSWINO_E_UNSUPPORTED = -2,          /* stride != 1, even modulus, modulus < 3 or > 65521, 8/16-bit mix,
+                                          K-sum too long for the 32-bit accumulator of the residue GEMM      */
+  RNSWINO_E_NOT_COPRIME = -3,          /* two moduli share a factor (section 3: pairwise coprime)           */
+  RNSWINO_E_POINT_NOT_INVERTIBLE = -4, /* a modulus shares a factor with a difference of two interpolation
+                                          points, so a denominator of V^-1 has no inverse (section 5)       */
+  RNSWINO_E_RANGE = -5,                /* 2^14 r^2 C exceeds (prod m_i - 1)/2: the dynamic range of the RNS
+                                          cannot hold the worst-case output (sections 3, 5, 8)              */
+  RNSWINO_E_HIP = -6,                  /* a HIP runtime call or kernel launch failed                        */
+  RNSWINO_E_NO_DEVICE = -7             /* the plan was made host-only, or no GPU is present                 */
+};
+
+enum {
+  RNSWINO_FLAG_ALLOW_UNCHECKED_RANGE = 1u, /* skip the worst-case range test: the caller vouches that every
+                                              output lies in [-(P-1)/2, (P-1)/2], P = prod m_i, as the paper
+                                              does with a measured range (section 8); otherwise the output
+                                              is the true result reduced to that interval (mod 2^32)       */
+  RNSWINO_FLAG_HOST_ONLY = 2u              /* build the host tables only (no GPU touched): such a plan can
+                                              be queried but not executed                                   */
+};
+
+typedef struct rnswino_plan_s rnswino_plan_t;   /* opaque, owned by the library */
+
+typedef struct {
+  int32_t  N, C, K, H, W;   /* activations x: int8 [N][C][H][W]                                              */
+  int32_t  r;               /* filter r x r; weights w: int8 [K][C][r][r]                                    */
+  int32_t  m;               /* output tile m x m; transform tile t = m + r - 1, 2 <= t <= 16                */
+  int32_t  pad;             /* zeros added on each side of H and W (>= 0)                                   */
+  int32_t  stride;          /* must be 1 (0 is read as 1)                                                    */
+  int32_t  n_moduli;        /* 1 .. 8                                                                        */
+  uint32_t moduli[8];       /* odd, pairwise coprime; either all in [3,253] (residues stored in 8 bits) or
+                               all in [257,65521] (16 bits)                                                  */
+  uint32_t flags;           /* RNSWINO_FLAG_*                                                                */
+} rnswino_desc_t;
+
+/* Transform matrices modulo one modulus, entries in [-(p-1)/2, (p-1)/2] (section 5):
+ * A^T is m x t, G is t x r, B^T is t x t, row-major. */
+enum { RNSWINO_MATRIX_AT = 0, RNSWINO_MATRIX_G = 1, RNSWINO_MATRIX_BT = 2 };
+
+/* Intermediate tensors of the pipeline (section 6), for stage-level checks. */
+enum { RNSWINO_STAGE_U = 0, RNSWINO_STAGE_V = 1, RNSWINO_STAGE_O = 2 };
+
+/*
+ * Build a plan (sections 4-5): interpolation points 0, +1, -1, +2, -2, ..., infinity; A^T, G, B^T modulo
+ * every modulus by exact modular arithmetic; checks (coprimality, invertibility of every point difference,
+ * dynamic range); mixed-radix constants; the transform tables the kernels read, uploaded to the current
+ * HIP device unless RNSWINO_FLAG_HOST_ONLY.  `desc` is host memory and is copied.  On error *out is NULL.
+ */
+int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc);
+int rnswino_plan_destroy(rnswino_plan_t *plan);
+
+/* Output plane size Ho = H + 2 pad - r + 1 (and Wo likewise); y is int32 [N][K][Ho][Wo]. */
+int rnswino_output_dims(const rnswino_plan_t *plan, int32_t *Ho, int32_t *Wo);
+
+/* Bytes of the transformed filter U (all residues, all t*t transform points) and of the workspace that
+ * holds the transformed input V and the GEMM output O.  0 if plan is NULL. */
+size_t rnswino_filter_bytes(const rnswino_plan_t *plan);
+size_t rnswino_workspace_bytes(const rnswino_plan_t *plan);
+
+/*
+ * Offline filter transform (section 6: "can be pre-calculated"):
+ *   U[i][xi,nu][k][c] = (G_p g^(c)(k) G_p^T)[xi,nu] mod m_i.
+ * w_dev: int8 [K][C][r][r].  U_dev: rnswino_filter_bytes() bytes, 256-byte aligned, written in the library's
+ * own tiled layout; it stays valid for any plan with the same C, K, r, m and moduli.
+ */
+int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, void *U_dev, void *stream);
+
+/*
+ * The layer (section 6): residues of x, input transform B^T d B per tile and residue, one GEMM over C per
+ * transform point and residue with the modulo after the sum, inverse transform A^T (.) A after that
+ * reduction, mixed-radix conversion to int32.
+ * x_dev: int8 [N][C][H][W].  U_dev: from rnswino_filter_transform.  y_dev: int32 [N][K][Ho][Wo].
+ * workspace_dev: rnswino_workspace_bytes() bytes, 256-byte aligned; contents are scratch.
+ * When the plan passed the range test, y equals the direct convolution
+ *   y[n][k][oy][ox] = sum_{c,i,j} xpad[n][c][oy+i-pad][ox+j-pad] * w[k][c][i][j]
+ * (correlation orientation of section 3.1) bit for bit.
+ */
+int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev,
+                   int32_t *y_dev, void *workspace_dev, void *stream);
+
+/*
+ * Glue for chaining layers (not part of the paper's method; the 13-layer stack workload needs it):
+ *   a = clamp(floor(y / 2^shift), -128, 127), optionally followed by a 2x2 stride-2 max-pool.
+ * y_dev: int32 [planes][H][W]; a_dev: int8 [planes][H][W], or [planes][H/2][W/2] when pool != 0 (H, W even).
+ */
+int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, int32_t H, int32_t W,
+                         int32_t shift, int32_t pool, void *stream);
+
+/* ---- query / test surface ---- */
+
+/* Copy one transform matrix (which = RNSWINO_MATRIX_*, modulus_idx < n_moduli) to host_out (row-major int32). */
+int rnswino_plan_get_matrix(const rnswino_plan_t *plan, int which, int modulus_idx, int32_t *host_out);
+
+/* Mixed-radix constant: inverse of moduli[l] modulo moduli[j] (l < j), in [0, moduli[j]). */
+int rnswino_plan_get_mrc_inverse(const rnswino_plan_t *plan, int l, int j, uint32_t *host_out);
+
+/* (prod m_i - 1)/2 saturated to 2^63-1: the largest magnitude the plan's RNS represents. */
+int64_t rnswino_plan_dynamic_range(const rnswino_plan_t *plan);
+
+/*
+ * Copy an intermediate tensor to HOST memory as int32 canonical residues in [-(p-1)/2, (p-1)/2], in the
+ * plain index order of section 6 (synchronises the device; test use only):
+ *   RNSWINO_STAGE_U: src_dev = U_dev,         host_out [n][t*t][K][C]
+ *   RNSWINO_STAGE_V: src_dev = workspace_dev, host_out [n][t*t][T][C],  T = N * ceil(Ho/m) * ceil(Wo/m)
+ *   RNSWINO_STAGE_O: src_dev = workspace_dev, host_out [n][t*t][K][T]
+ * Tile index tau = (n * th + ty) * tw + tx.
+ */
+int rnswino_debug_stage(const rnswino_plan_t *plan, int stage, const void *src_dev, int32_t *host_out);
+
+const char *rnswino_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNSWINO_H */

@@ -1,0 +1,189 @@
+"""ctypes binding with the same names as include/rnswino.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "librnswino.so")
+
+MATRIX_AT, MATRIX_G, MATRIX_BT = 0, 1, 2
+STAGE_U, STAGE_V, STAGE_O = 0, 1, 2
+FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY = 1, 2
+
+EXPORTED_SYMBOLS = (
+    "rnswino_plan", "rnswino_plan_destroy", "rnswino_output_dims", "rnswino_filter_bytes",
+    "rnswino_workspace_bytes", "rnswino_filter_transform", "rnswino_conv2d", "rnswino_requant_pool",
+    "rnswino_plan_get_matrix", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
+    "rnswino_debug_stage", "rnswino_strerror",
+)
+
+
+class RnsWinoError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {rnswino_strerror(code)} ({code})")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("C", ctypes.c_int32), ("K", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("W", ctypes.c_int32), ("r", ctypes.c_int32), ("m", ctypes.c_int32), ("pad", ctypes.c_int32),
+                ("stride", ctypes.c_int32), ("n_moduli", ctypes.c_int32), ("moduli", ctypes.c_uint32 * 8),
+                ("flags", ctypes.c_uint32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Load librnswino.so (built in-tree).  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2007_12216_amd.build` "
+                              "(or __graft_entry__.build())")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32
+        L.rnswino_plan.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(_Desc)]
+        L.rnswino_plan.restype = ctypes.c_int
+        L.rnswino_plan_destroy.argtypes = [vp]
+        L.rnswino_plan_destroy.restype = ctypes.c_int
+        L.rnswino_output_dims.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.rnswino_output_dims.restype = ctypes.c_int
+        L.rnswino_filter_bytes.argtypes = [vp]
+        L.rnswino_filter_bytes.restype = ctypes.c_size_t
+        L.rnswino_workspace_bytes.argtypes = [vp]
+        L.rnswino_workspace_bytes.restype = ctypes.c_size_t
+        L.rnswino_filter_transform.argtypes = [vp, vp, vp, vp]
+        L.rnswino_filter_transform.restype = ctypes.c_int
+        L.rnswino_conv2d.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.rnswino_conv2d.restype = ctypes.c_int
+        L.rnswino_requant_pool.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp]
+        L.rnswino_requant_pool.restype = ctypes.c_int
+        L.rnswino_plan_get_matrix.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
+        L.rnswino_plan_get_matrix.restype = ctypes.c_int
+        L.rnswino_plan_get_mrc_inverse.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(u32)]
+        L.rnswino_plan_get_mrc_inverse.restype = ctypes.c_int
+        L.rnswino_plan_dynamic_range.argtypes = [vp]
+        L.rnswino_plan_dynamic_range.restype = i64
+        L.rnswino_debug_stage.argtypes = [vp, ctypes.c_int, vp, vp]
+        L.rnswino_debug_stage.restype = ctypes.c_int
+        L.rnswino_strerror.argtypes = [ctypes.c_int]
+        L.rnswino_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def rnswino_strerror(code: int) -> str:
+    return lib().rnswino_strerror(int(code)).decode()
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise RnsWinoError(code, what)
+
+
+class Plan:
+    """Owner of one rnswino_plan_t* (destroyed with the object)."""
+
+    def __init__(self, handle, desc):
+        self.handle = handle
+        self.N, self.C, self.K, self.H, self.W = desc.N, desc.C, desc.K, desc.H, desc.W
+        self.r, self.m, self.pad = desc.r, desc.m, desc.pad
+        self.t = desc.m + desc.r - 1
+        self.moduli = tuple(desc.moduli[i] for i in range(desc.n_moduli))
+        self.Ho, self.Wo = rnswino_output_dims(self)
+        self.th, self.tw = -(-self.Ho // self.m), -(-self.Wo // self.m)
+        self.T = self.N * self.th * self.tw
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.rnswino_plan_destroy(h)
+
+
+def rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags: int = 0, stride: int = 1) -> Plan:
+    d = _Desc()
+    d.N, d.C, d.K, d.H, d.W, d.r, d.m, d.pad, d.stride = N, C, K, H, W, r, m, pad, stride
+    d.n_moduli = len(moduli)
+    if len(moduli) <= 8:
+        for i, p in enumerate(moduli):
+            d.moduli[i] = p
+    d.flags = flags
+    out = ctypes.c_void_p()
+    _check(lib().rnswino_plan(ctypes.byref(out), ctypes.byref(d)), "rnswino_plan")
+    return Plan(out, d)
+
+
+def rnswino_plan_destroy(plan: Plan) -> None:
+    h, plan.handle = plan.handle, None
+    if h:
+        _check(lib().rnswino_plan_destroy(h), "rnswino_plan_destroy")
+
+
+def rnswino_output_dims(plan: Plan):
+    ho, wo = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().rnswino_output_dims(plan.handle, ctypes.byref(ho), ctypes.byref(wo)), "rnswino_output_dims")
+    return ho.value, wo.value
+
+
+def rnswino_filter_bytes(plan: Plan) -> int:
+    return int(lib().rnswino_filter_bytes(plan.handle))
+
+
+def rnswino_workspace_bytes(plan: Plan) -> int:
+    return int(lib().rnswino_workspace_bytes(plan.handle))
+
+
+def _ptr(obj) -> int:
+    """Device (or host) address of a torch tensor / numpy array / raw int."""
+    if isinstance(obj, int):
+        return obj
+    if hasattr(obj, "data_ptr"):
+        return obj.data_ptr()
+    return obj.ctypes.data
+
+
+def rnswino_filter_transform(plan: Plan, w_dev, U_dev, stream: int = 0) -> None:
+    _check(lib().rnswino_filter_transform(plan.handle, _ptr(w_dev), _ptr(U_dev), stream), "rnswino_filter_transform")
+
+
+def rnswino_conv2d(plan: Plan, x_dev, U_dev, y_dev, workspace_dev, stream: int = 0) -> None:
+    _check(lib().rnswino_conv2d(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev), _ptr(workspace_dev), stream),
+           "rnswino_conv2d")
+
+
+def rnswino_requant_pool(y_dev, a_dev, planes: int, H: int, W: int, shift: int, pool: bool, stream: int = 0) -> None:
+    _check(lib().rnswino_requant_pool(_ptr(y_dev), _ptr(a_dev), planes, H, W, shift, int(bool(pool)), stream),
+           "rnswino_requant_pool")
+
+
+def rnswino_plan_get_matrix(plan: Plan, which: int, modulus_idx: int) -> np.ndarray:
+    shape = {MATRIX_AT: (plan.m, plan.t), MATRIX_G: (plan.t, plan.r), MATRIX_BT: (plan.t, plan.t)}.get(which, (1, 1))
+    out = np.zeros(shape, dtype=np.int32)
+    _check(lib().rnswino_plan_get_matrix(plan.handle, which, modulus_idx, out.ctypes.data), "rnswino_plan_get_matrix")
+    return out
+
+
+def rnswino_plan_get_mrc_inverse(plan: Plan, l: int, j: int) -> int:
+    v = ctypes.c_uint32()
+    _check(lib().rnswino_plan_get_mrc_inverse(plan.handle, l, j, ctypes.byref(v)), "rnswino_plan_get_mrc_inverse")
+    return v.value
+
+
+def rnswino_plan_dynamic_range(plan: Plan) -> int:
+    return int(lib().rnswino_plan_dynamic_range(plan.handle))
+
+
+def rnswino_debug_stage(plan: Plan, stage: int, src_dev) -> np.ndarray:
+    n, P2 = len(plan.moduli), plan.t * plan.t
+    shape = {STAGE_U: (n, P2, plan.K, plan.C), STAGE_V: (n, P2, plan.T, plan.C), STAGE_O: (n, P2, plan.K, plan.T)}[stage]
+    out = np.empty(shape, dtype=np.int32)
+    _check(lib().rnswino_debug_stage(plan.handle, stage, _ptr(src_dev), out.ctypes.data), "rnswino_debug_stage")
+    return out

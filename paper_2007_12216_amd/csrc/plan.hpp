@@ -1,0 +1,48 @@
+// Internal plan structure of the rnswino library (host side).
+#pragma once
+#include <cstdint>
+#include <vector>
+#include "rnswino.h"
+
+namespace rnswino {
+
+// Derived sizes of a layer.  Paper notation: t is N = M + R - 1 of section 4.
+struct Dims {
+  int N, C, K, H, W, r, m, t, pad;
+  int Ho, Wo, th, tw, T;     // output plane, tiles per image, tiles in total
+  int n;                     // number of moduli
+  int wide;                  // 0: moduli < 256 (residues in 8 bits), 1: 16-bit moduli
+  int Cp, Kp, Tp;            // C padded to 64, K and T padded to 16 (tiled tensor extents)
+  int P2;                    // t*t transform points
+  int Q;                     // ceil(t*t / 4): groups of four transform points in the O tensor
+};
+
+// Transform matrices modulo one modulus, entries symmetric in [-(p-1)/2, (p-1)/2].
+struct Transforms {
+  std::vector<int32_t> AT;   // m x t
+  std::vector<int32_t> G;    // t x r
+  std::vector<int32_t> BT;   // t x t
+};
+
+// Exact modular helpers (plan_math.cpp).
+int64_t mod_inverse(int64_t a, int64_t p);              // -1 when gcd(a, p) != 1
+int32_t sym_residue(int64_t v, int64_t p);              // representative in [-(p-1)/2, (p-1)/2]
+std::vector<int> interpolation_points(int t);           // the t-1 finite points 0, 1, -1, 2, -2, ...
+int build_transforms(int m, int r, uint32_t p, Transforms &out);   // RNSWINO_OK or an error code
+int validate_desc(const rnswino_desc_t &d, Dims &dims);            // fills dims; all host-side checks
+
+}  // namespace rnswino
+
+struct rnswino_plan_s {
+  rnswino_desc_t desc;
+  rnswino::Dims dims;
+  std::vector<rnswino::Transforms> tf;      // one per modulus
+  uint32_t mrc_inv[8][8];                   // mrc_inv[l][j] = moduli[l]^-1 mod moduli[j], l < j
+  int64_t dyn_range;                        // (prod - 1)/2, saturated
+  int device;                               // HIP device the tables live on, -1 for host-only plans
+  void *d_tables;                           // one device allocation holding every table below
+  size_t d_tables_bytes;
+  // offsets (bytes) into d_tables
+  size_t off_AT, off_G, off_BT;             // int32 matrices, [n][...]
+  size_t off_KB, off_KA;                    // int8 Kronecker tables for the MFMA transforms (see kernels)
+};

@@ -1,0 +1,543 @@
+// rnswino: C ABI entry points and HIP kernels (gfx950).
+//
+// Pipeline of one layer (paper section 6):
+//   K0  filter transform   U = G g G^T mod p                 (offline, once per weight set)
+//   K1  input transform    V = B^T d B mod p                 (per tile, channel, residue)
+//   K2  residue GEMM       O = sum_c U V mod p               (per transform point and residue; int8 MFMA)
+//   K3  inverse transform  Y = A^T O A mod p, then mixed-radix conversion to int32
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "layout.hpp"
+#include "plan.hpp"
+#include "rnswino.h"
+
+using namespace rnswino;
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Everything a kernel needs to know about the layer, passed by value.
+struct KParams {
+  int N, C, K, H, W, r, m, t, pad;
+  int Ho, Wo, th, tw, T, n;
+  int Cp, Kp, Tp, P2, Q;
+  int p[8];
+  float inv_p[8];
+  int mrc_inv[8][8];          // mrc_inv[l][j] = p_l^-1 mod p_j  (l < j)
+  const int32_t *AT, *G, *BT; // device tables [n][m*t], [n][t*r], [n][t*t]
+};
+
+// ---------------------------------------------------------------------------------------------
+// modular helpers
+// ---------------------------------------------------------------------------------------------
+
+// exact symmetric residue of a 64-bit value (slow; used off the hot path)
+__device__ __forceinline__ int sym_mod64(long long v, int p) {
+  int r = (int)(v % p);
+  const int h = (p - 1) >> 1;
+  if (r > h) r -= p;
+  if (r < -h) r += p;
+  return r;
+}
+
+// Residue of x modulo p for |x| < 2^24 and p <= 253, without division: q = rint(x/p) from one fused
+// multiply-add against 1.5*2^23 (whose mantissa then holds q), r = x - q p.  1/p carries a relative error
+// of 2^-24, so |x/p - q| <= 1/2 + |x| 2^-24 / p and |r| <= p/2 + 1: a valid representative that fits int8
+// (|r| <= 127), not always the canonical one.
+__device__ __forceinline__ int mod_near(int x, float inv_p, int p) {
+  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
+  const int q = __float_as_int(f) - 0x4B400000;
+  return x - __mul24(q, p);
+}
+
+// ---------------------------------------------------------------------------------------------
+// K0: filter transform (offline).  One thread per (residue, k, c) of the padded K x C grid.
+// ---------------------------------------------------------------------------------------------
+template <typename RT>
+__global__ void k0_filter_transform(KParams P, const int8_t *__restrict__ w, RT *__restrict__ U) {
+  const long long total = (long long)P.n * P.Kp * P.Cp;
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % P.Cp); idx /= P.Cp;
+  const int k = (int)(idx % P.Kp);
+  const int i = (int)(idx / P.Kp);
+  const int p = P.p[i], t = P.t, r = P.r;
+  const int32_t *G = P.G + (size_t)i * t * r;
+  int g[25];
+  const bool live = (k < P.K) && (c < P.C);
+  for (int e = 0; e < r * r; ++e) g[e] = live ? (int)w[((size_t)k * P.C + c) * r * r + e] : 0;
+  for (int xi = 0; xi < t; ++xi) {
+    long long row[5];
+    for (int b = 0; b < r; ++b) {
+      long long s = 0;
+      for (int a = 0; a < r; ++a) s += (long long)G[xi * r + a] * g[a * r + b];
+      row[b] = s;
+    }
+    for (int nu = 0; nu < t; ++nu) {
+      long long s = 0;
+      for (int b = 0; b < r; ++b) s += row[b] * G[nu * r + b];
+      U[u_offset(i * P.P2 + xi * t + nu, k, c, P.Kp, P.Cp)] = (RT)sym_mod64(s, p);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K1 (plain version): one thread per (residue, tile, channel, column nu) computes column nu of B^T d B.
+// ---------------------------------------------------------------------------------------------
+template <typename RT>
+__global__ void k1_input_transform_plain(KParams P, const int8_t *__restrict__ x, RT *__restrict__ V) {
+  const int t = P.t;
+  const long long total = (long long)P.n * P.T * P.Cp * t;
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % P.Cp); idx /= P.Cp;
+  const int nu = (int)(idx % t); idx /= t;
+  const int tau = (int)(idx % P.T);
+  const int i = (int)(idx / P.T);
+  const int p = P.p[i];
+  const int32_t *BT = P.BT + (size_t)i * t * t;
+  if (c >= P.C) {
+    for (int xi = 0; xi < t; ++xi) V[v_offset(i * P.P2 + xi * t + nu, tau, c, P.Tp, P.Cp)] = 0;
+    return;
+  }
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
+  const int8_t *plane = x + ((size_t)img * P.C + c) * P.H * P.W;
+  int e[16];
+  for (int a = 0; a < t; ++a) {
+    long long s = 0;
+    const int gy = y0 + a;
+    if (gy >= 0 && gy < P.H)
+      for (int b = 0; b < t; ++b) {
+        const int gx = x0 + b;
+        if (gx >= 0 && gx < P.W) s += (long long)plane[(size_t)gy * P.W + gx] * BT[nu * t + b];
+      }
+    e[a] = sym_mod64(s, p);
+  }
+  for (int xi = 0; xi < t; ++xi) {
+    long long s = 0;
+    for (int a = 0; a < t; ++a) s += (long long)BT[xi * t + a] * e[a];
+    V[v_offset(i * P.P2 + xi * t + nu, tau, c, P.Tp, P.Cp)] = (RT)sym_mod64(s, p);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K2, 8-bit moduli: O = U V^T mod p on v_mfma_i32_16x16x64_i8.
+// Block = 4 waves = the 4 transform points of one group q (they end up as the 4 bytes of one O word);
+// every wave computes a 32 (k) x 64 (tile) block of its point over the whole of C.
+// Grid: x = n*Q, y = ceil(Kp/32), z = ceil(Tp/64).
+// KS = contraction steps (of 64 channels) whose operand fragments are loaded before any is consumed.
+// ---------------------------------------------------------------------------------------------
+template <int KS>
+__global__ __launch_bounds__(256) void k2_gemm_i8(KParams P, const int8_t *__restrict__ U,
+                                                   const int8_t *__restrict__ V, uint32_t *__restrict__ O) {
+  __shared__ uint32_t tile[32 * 64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x / P.Q, q = blockIdx.x % P.Q;
+  const int pt = 4 * q + wave;
+  const int nkb = P.Kp >> 4, ntb = P.Tp >> 4, ncb = P.Cp >> 6;
+  const int kb0 = blockIdx.y * 2, tb0 = blockIdx.z * 4;
+  const int p = P.p[i];
+  const float inv = P.inv_p[i];
+
+  v4i acc[2][4];
+#pragma unroll
+  for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) acc[rm][tb] = (v4i){0, 0, 0, 0};
+
+  if (pt < P.P2) {
+    const int slab = i * P.P2 + pt;
+    const int8_t *Ub = U + (size_t)slab * nkb * ncb * 1024 + lane * 16;
+    const int8_t *Vb = V + (size_t)slab * P.Tp * P.Cp + (size_t)(lane & 15) * P.Cp + (lane >> 4) * 16;
+    for (int s0 = 0; s0 < ncb; s0 += KS) {
+      v4i a[KS][2], b[KS][4];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int rm = 0; rm < 2; ++rm) {
+          a[s][rm] = (v4i){0, 0, 0, 0};
+          if (kb0 + rm < nkb) a[s][rm] = *(const v4i *)(Ub + ((size_t)(kb0 + rm) * ncb + s0 + s) * 1024);
+        }
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+          b[s][tb] = (v4i){0, 0, 0, 0};
+          if (tb0 + tb < ntb) b[s][tb] = *(const v4i *)(Vb + (size_t)(tb0 + tb) * 16 * P.Cp + (s0 + s) * 64);
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+          for (int tb = 0; tb < 4; ++tb)
+            acc[rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm], b[s][tb], acc[rm][tb], 0, 0, 0);
+      // |U|,|V| <= 127: 512 channels add at most 8.3e6, so reducing every 8 steps keeps |acc| < 2^24
+      if ((((s0 + KS) & 7) == 0) && (s0 + KS < ncb)) {
+#pragma unroll
+        for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+          for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[rm][tb][j] = mod_near(acc[rm][tb][j], inv, p);
+      }
+    }
+  }
+
+  uint8_t *tile8 = (uint8_t *)tile;
+#pragma unroll
+  for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = rm * 16 + 4 * (lane >> 4) + j, col = tb * 16 + (lane & 15);
+        tile8[(row * 64 + col) * 4 + wave] = (uint8_t)mod_near(acc[rm][tb][j], inv, p);
+      }
+  __syncthreads();
+  uint32_t *Ob = O + ((size_t)i * P.Q + q) * P.Kp * P.Tp;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int e = it * 256 + threadIdx.x;
+    const int row = e >> 6, col = e & 63;
+    const int k = kb0 * 16 + row, tau = tb0 * 16 + col;
+    if (k < P.Kp && tau < P.Tp) Ob[(size_t)k * P.Tp + tau] = tile[e];
+  }
+}
+
+// K2 (plain version, any modulus width): one thread per output element, 64-bit accumulation.
+template <typename RT>
+__global__ void k2_gemm_plain(KParams P, const RT *__restrict__ U, const RT *__restrict__ V, RT *__restrict__ O) {
+  const long long total = (long long)P.n * P.P2 * P.K * P.T;
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int tau = (int)(idx % P.T); idx /= P.T;
+  const int k = (int)(idx % P.K); idx /= P.K;
+  const int pt = (int)(idx % P.P2);
+  const int i = (int)(idx / P.P2);
+  long long s = 0;
+  for (int c = 0; c < P.C; ++c)
+    s += (long long)U[u_offset(i * P.P2 + pt, k, c, P.Kp, P.Cp)] * (long long)V[v_offset(i * P.P2 + pt, tau, c, P.Tp, P.Cp)];
+  O[o_offset(i, pt, k, tau, P.Q, P.Kp, P.Tp)] = (RT)sym_mod64(s, P.p[i]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// K3 (plain version): one thread per (k, tile, output column v): column v of A^T O A for every residue,
+// then mixed-radix conversion (symmetric digits) and the store of m outputs.
+// ---------------------------------------------------------------------------------------------
+template <typename RT>
+__global__ void k3_inverse_mrc_plain(KParams P, const RT *__restrict__ O, int32_t *__restrict__ y) {
+  const int t = P.t, m = P.m;
+  const long long total = (long long)P.K * P.T * m;
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int tau = (int)(idx % P.T); idx /= P.T;
+  const int v = (int)(idx % m);
+  const int k = (int)(idx / m);
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  const int ox = tx * m + v;
+  if (ox >= P.Wo) return;
+  int digits[8];
+  for (int u = 0; u < m; ++u) {
+    const int oy = ty * m + u;
+    if (oy >= P.Ho) break;
+    for (int i = 0; i < P.n; ++i) {
+      const int p = P.p[i];
+      const int32_t *AT = P.AT + (size_t)i * m * t;
+      long long s = 0;
+      for (int xi = 0; xi < t; ++xi) {
+        long long e = 0;
+        for (int nu = 0; nu < t; ++nu)
+          e += (long long)O[o_offset(i, xi * t + nu, k, tau, P.Q, P.Kp, P.Tp)] * AT[v * t + nu];
+        s += (long long)AT[u * t + xi] * sym_mod64(e, p);
+      }
+      long long d = sym_mod64(s, p);
+      for (int l = 0; l < i; ++l) d = sym_mod64((d - digits[l]) * (long long)P.mrc_inv[l][i], p);
+      digits[i] = (int)d;
+    }
+    uint32_t val = (uint32_t)digits[P.n - 1];
+    for (int j = P.n - 2; j >= 0; --j) val = (uint32_t)digits[j] + (uint32_t)P.p[j] * val;
+    y[(((size_t)img * P.K + k) * P.Ho + oy) * P.Wo + ox] = (int32_t)val;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Layer glue: a = clamp(y >> shift, -128, 127), optional 2x2 max-pool.
+// ---------------------------------------------------------------------------------------------
+__global__ void k_requant_pool(const int32_t *__restrict__ y, int8_t *__restrict__ a, long long planes, int H, int W,
+                               int shift, int pool) {
+  const int Hq = pool ? H / 2 : H, Wq = pool ? W / 2 : W;
+  const long long total = planes * Hq * Wq;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int xx = (int)(idx % Wq);
+    const int yy = (int)((idx / Wq) % Hq);
+    const long long pl = idx / ((long long)Wq * Hq);
+    int best;
+    if (pool) {
+      const int32_t *src = y + (pl * H + 2 * yy) * W + 2 * xx;
+      best = max(max(src[0], src[1]), max(src[W], src[W + 1]));
+    } else {
+      best = y[idx];
+    }
+    best >>= shift;   // arithmetic shift: floor division; monotone, so it commutes with the max
+    best = min(127, max(-128, best));
+    a[idx] = (int8_t)best;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+
+KParams make_params(const rnswino_plan_t *pl) {
+  KParams P;
+  std::memset(&P, 0, sizeof(P));
+  const Dims &d = pl->dims;
+  P.N = d.N; P.C = d.C; P.K = d.K; P.H = d.H; P.W = d.W; P.r = d.r; P.m = d.m; P.t = d.t; P.pad = d.pad;
+  P.Ho = d.Ho; P.Wo = d.Wo; P.th = d.th; P.tw = d.tw; P.T = d.T; P.n = d.n;
+  P.Cp = d.Cp; P.Kp = d.Kp; P.Tp = d.Tp; P.P2 = d.P2; P.Q = d.Q;
+  for (int i = 0; i < d.n; ++i) {
+    P.p[i] = (int)pl->desc.moduli[i];
+    P.inv_p[i] = 1.0f / (float)pl->desc.moduli[i];
+    for (int j = 0; j < d.n; ++j) P.mrc_inv[i][j] = (int)pl->mrc_inv[i][j];
+  }
+  const char *base = (const char *)pl->d_tables;
+  P.AT = (const int32_t *)(base + pl->off_AT);
+  P.G = (const int32_t *)(base + pl->off_G);
+  P.BT = (const int32_t *)(base + pl->off_BT);
+  return P;
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline size_t elem_bytes(const Dims &d) { return d.wide ? 2 : 1; }
+inline size_t v_bytes(const Dims &d) { return (size_t)d.n * d.P2 * d.Tp * d.Cp * elem_bytes(d); }
+inline size_t o_bytes(const Dims &d) { return (size_t)d.n * d.Q * d.Kp * d.Tp * 4 * elem_bytes(d); }
+inline size_t u_bytes(const Dims &d) { return (size_t)d.n * d.P2 * d.Kp * d.Cp * elem_bytes(d); }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? RNSWINO_OK : RNSWINO_E_HIP; }
+
+inline unsigned blocks_for(long long total, int bs) { return (unsigned)((total + bs - 1) / bs); }
+
+}  // namespace
+
+// =============================================================================================
+// C ABI
+// =============================================================================================
+
+extern "C" {
+
+int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
+  if (out) *out = nullptr;
+  if (!out || !desc) return RNSWINO_E_INVALID;
+  rnswino_plan_t *pl = new (std::nothrow) rnswino_plan_t();
+  if (!pl) return RNSWINO_E_INVALID;
+  pl->desc = *desc;
+  pl->device = -1;
+  pl->d_tables = nullptr;
+  pl->d_tables_bytes = 0;
+  int rc = validate_desc(*desc, pl->dims);
+  if (rc != RNSWINO_OK) { delete pl; return rc; }
+  const Dims &d = pl->dims;
+  pl->tf.resize(d.n);
+  for (int i = 0; i < d.n; ++i) {
+    rc = build_transforms(d.m, d.r, desc->moduli[i], pl->tf[i]);
+    if (rc != RNSWINO_OK) { delete pl; return rc; }
+  }
+  // dynamic range (prod - 1)/2, saturated, against the worst case 2^14 r^2 C (sections 3, 5, 8)
+  unsigned __int128 prod = 1;
+  const unsigned __int128 cap = ((unsigned __int128)1 << 100);
+  for (int i = 0; i < d.n; ++i) { prod *= desc->moduli[i]; if (prod > cap) prod = cap; }
+  const unsigned __int128 half = (prod - 1) / 2;
+  pl->dyn_range = half > (unsigned __int128)INT64_MAX ? INT64_MAX : (int64_t)half;
+  const unsigned __int128 worst = (unsigned __int128)16384u * (unsigned)d.r * (unsigned)d.r * (unsigned)d.C;
+  if (!(desc->flags & RNSWINO_FLAG_ALLOW_UNCHECKED_RANGE) && worst > half) { delete pl; return RNSWINO_E_RANGE; }
+  std::memset(pl->mrc_inv, 0, sizeof(pl->mrc_inv));
+  for (int l = 0; l < d.n; ++l)
+    for (int j = l + 1; j < d.n; ++j) pl->mrc_inv[l][j] = (uint32_t)mod_inverse(desc->moduli[l], desc->moduli[j]);
+
+  // device tables
+  const size_t szAT = (size_t)d.n * d.m * d.t * 4, szG = (size_t)d.n * d.t * d.r * 4, szBT = (size_t)d.n * d.t * d.t * 4;
+  pl->off_AT = 0;
+  pl->off_G = align256(pl->off_AT + szAT);
+  pl->off_BT = align256(pl->off_G + szG);
+  pl->off_KB = pl->off_KA = 0;
+  pl->d_tables_bytes = align256(pl->off_BT + szBT);
+  if (!(desc->flags & RNSWINO_FLAG_HOST_ONLY)) {
+    std::vector<char> host(pl->d_tables_bytes, 0);
+    for (int i = 0; i < d.n; ++i) {
+      std::memcpy(host.data() + pl->off_AT + (size_t)i * d.m * d.t * 4, pl->tf[i].AT.data(), (size_t)d.m * d.t * 4);
+      std::memcpy(host.data() + pl->off_G + (size_t)i * d.t * d.r * 4, pl->tf[i].G.data(), (size_t)d.t * d.r * 4);
+      std::memcpy(host.data() + pl->off_BT + (size_t)i * d.t * d.t * 4, pl->tf[i].BT.data(), (size_t)d.t * d.t * 4);
+    }
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); delete pl; return RNSWINO_E_NO_DEVICE; }
+    if (hipMalloc(&pl->d_tables, pl->d_tables_bytes) != hipSuccess) { (void)hipGetLastError(); delete pl; return RNSWINO_E_HIP; }
+    if (hipMemcpy(pl->d_tables, host.data(), pl->d_tables_bytes, hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP;
+    }
+    pl->device = dev;
+  }
+  *out = pl;
+  return RNSWINO_OK;
+}
+
+int rnswino_plan_destroy(rnswino_plan_t *plan) {
+  if (!plan) return RNSWINO_E_INVALID;
+  int rc = RNSWINO_OK;
+  if (plan->d_tables && hipFree(plan->d_tables) != hipSuccess) { (void)hipGetLastError(); rc = RNSWINO_E_HIP; }
+  delete plan;
+  return rc;
+}
+
+int rnswino_output_dims(const rnswino_plan_t *plan, int32_t *Ho, int32_t *Wo) {
+  if (!plan || !Ho || !Wo) return RNSWINO_E_INVALID;
+  *Ho = plan->dims.Ho; *Wo = plan->dims.Wo;
+  return RNSWINO_OK;
+}
+
+size_t rnswino_filter_bytes(const rnswino_plan_t *plan) { return plan ? align256(u_bytes(plan->dims)) : 0; }
+
+size_t rnswino_workspace_bytes(const rnswino_plan_t *plan) {
+  return plan ? align256(v_bytes(plan->dims)) + align256(o_bytes(plan->dims)) : 0;
+}
+
+int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, void *U_dev, void *stream) {
+  if (!plan || !w_dev || !U_dev) return RNSWINO_E_INVALID;
+  if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
+  const Dims &d = plan->dims;
+  const KParams P = make_params(plan);
+  const long long total = (long long)d.n * d.Kp * d.Cp;
+  hipStream_t st = (hipStream_t)stream;
+  if (d.wide)
+    hipLaunchKernelGGL(k0_filter_transform<int16_t>, dim3(blocks_for(total, 256)), dim3(256), 0, st, P, w_dev, (int16_t *)U_dev);
+  else
+    hipLaunchKernelGGL(k0_filter_transform<int8_t>, dim3(blocks_for(total, 256)), dim3(256), 0, st, P, w_dev, (int8_t *)U_dev);
+  return launch_status();
+}
+
+int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
+                   void *workspace_dev, void *stream) {
+  if (!plan || !x_dev || !U_dev || !y_dev || !workspace_dev) return RNSWINO_E_INVALID;
+  if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
+  const Dims &d = plan->dims;
+  const KParams P = make_params(plan);
+  hipStream_t st = (hipStream_t)stream;
+  char *Vp = (char *)workspace_dev;
+  char *Op = Vp + align256(v_bytes(d));
+
+  const long long t1 = (long long)d.n * d.T * d.Cp * d.t;
+  const long long t3 = (long long)d.K * d.T * d.m;
+  if (d.wide) {
+    hipLaunchKernelGGL(k1_input_transform_plain<int16_t>, dim3(blocks_for(t1, 256)), dim3(256), 0, st, P, x_dev, (int16_t *)Vp);
+    const long long t2 = (long long)d.n * d.P2 * d.K * d.T;
+    hipLaunchKernelGGL(k2_gemm_plain<int16_t>, dim3(blocks_for(t2, 256)), dim3(256), 0, st, P, (const int16_t *)U_dev,
+                       (const int16_t *)Vp, (int16_t *)Op);
+    hipLaunchKernelGGL(k3_inverse_mrc_plain<int16_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int16_t *)Op, y_dev);
+  } else {
+    hipLaunchKernelGGL(k1_input_transform_plain<int8_t>, dim3(blocks_for(t1, 256)), dim3(256), 0, st, P, x_dev, (int8_t *)Vp);
+    const dim3 grid((unsigned)(d.n * d.Q), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp + 63) / 64));
+    const int ncb = d.Cp / 64;
+    if (ncb % 4 == 0)
+      hipLaunchKernelGGL(k2_gemm_i8<4>, grid, dim3(256), 0, st, P, (const int8_t *)U_dev, (const int8_t *)Vp, (uint32_t *)Op);
+    else if (ncb % 2 == 0)
+      hipLaunchKernelGGL(k2_gemm_i8<2>, grid, dim3(256), 0, st, P, (const int8_t *)U_dev, (const int8_t *)Vp, (uint32_t *)Op);
+    else
+      hipLaunchKernelGGL(k2_gemm_i8<1>, grid, dim3(256), 0, st, P, (const int8_t *)U_dev, (const int8_t *)Vp, (uint32_t *)Op);
+    hipLaunchKernelGGL(k3_inverse_mrc_plain<int8_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int8_t *)Op, y_dev);
+  }
+  return launch_status();
+}
+
+int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, int32_t H, int32_t W, int32_t shift,
+                         int32_t pool, void *stream) {
+  if (!y_dev || !a_dev || planes <= 0 || H <= 0 || W <= 0 || shift < 0 || shift > 31) return RNSWINO_E_INVALID;
+  if (pool && ((H | W) & 1)) return RNSWINO_E_INVALID;
+  const long long total = (long long)planes * (pool ? H / 2 : H) * (pool ? W / 2 : W);
+  unsigned blocks = blocks_for(total, 256);
+  if (blocks > 65536u * 4u) blocks = 65536u * 4u;
+  hipLaunchKernelGGL(k_requant_pool, dim3(blocks), dim3(256), 0, (hipStream_t)stream, y_dev, a_dev, (long long)planes, H, W,
+                     shift, pool);
+  return launch_status();
+}
+
+int rnswino_plan_get_matrix(const rnswino_plan_t *plan, int which, int modulus_idx, int32_t *host_out) {
+  if (!plan || !host_out || modulus_idx < 0 || modulus_idx >= plan->dims.n) return RNSWINO_E_INVALID;
+  const Transforms &tf = plan->tf[modulus_idx];
+  const std::vector<int32_t> *src = which == RNSWINO_MATRIX_AT ? &tf.AT : which == RNSWINO_MATRIX_G ? &tf.G
+                                    : which == RNSWINO_MATRIX_BT ? &tf.BT : nullptr;
+  if (!src) return RNSWINO_E_INVALID;
+  std::memcpy(host_out, src->data(), src->size() * sizeof(int32_t));
+  return RNSWINO_OK;
+}
+
+int rnswino_plan_get_mrc_inverse(const rnswino_plan_t *plan, int l, int j, uint32_t *host_out) {
+  if (!plan || !host_out || l < 0 || j <= l || j >= plan->dims.n) return RNSWINO_E_INVALID;
+  *host_out = plan->mrc_inv[l][j];
+  return RNSWINO_OK;
+}
+
+int64_t rnswino_plan_dynamic_range(const rnswino_plan_t *plan) { return plan ? plan->dyn_range : 0; }
+
+int rnswino_debug_stage(const rnswino_plan_t *plan, int stage, const void *src_dev, int32_t *host_out) {
+  if (!plan || !src_dev || !host_out) return RNSWINO_E_INVALID;
+  if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
+  const Dims &d = plan->dims;
+  const size_t es = elem_bytes(d);
+  size_t bytes, skip = 0;
+  if (stage == RNSWINO_STAGE_U) bytes = u_bytes(d);
+  else if (stage == RNSWINO_STAGE_V) bytes = v_bytes(d);
+  else if (stage == RNSWINO_STAGE_O) { bytes = o_bytes(d); skip = align256(v_bytes(d)); }
+  else return RNSWINO_E_INVALID;
+  std::vector<char> raw(bytes);
+  if (hipDeviceSynchronize() != hipSuccess ||
+      hipMemcpy(raw.data(), (const char *)src_dev + skip, bytes, hipMemcpyDeviceToHost) != hipSuccess) {
+    (void)hipGetLastError();
+    return RNSWINO_E_HIP;
+  }
+  auto fetch = [&](size_t off) -> int64_t {
+    return es == 1 ? (int64_t)((const int8_t *)raw.data())[off] : (int64_t)((const int16_t *)raw.data())[off];
+  };
+  for (int i = 0; i < d.n; ++i) {
+    const int64_t p = plan->desc.moduli[i];
+    for (int pt = 0; pt < d.P2; ++pt) {
+      const int slab = i * d.P2 + pt;
+      if (stage == RNSWINO_STAGE_U) {
+        for (int k = 0; k < d.K; ++k)
+          for (int c = 0; c < d.C; ++c)
+            host_out[((size_t)slab * d.K + k) * d.C + c] = sym_residue(fetch(u_offset(slab, k, c, d.Kp, d.Cp)), p);
+      } else if (stage == RNSWINO_STAGE_V) {
+        for (int tau = 0; tau < d.T; ++tau)
+          for (int c = 0; c < d.C; ++c)
+            host_out[((size_t)slab * d.T + tau) * d.C + c] = sym_residue(fetch(v_offset(slab, tau, c, d.Tp, d.Cp)), p);
+      } else {
+        for (int k = 0; k < d.K; ++k)
+          for (int tau = 0; tau < d.T; ++tau)
+            host_out[((size_t)slab * d.K + k) * d.T + tau] = sym_residue(fetch(o_offset(i, pt, k, tau, d.Q, d.Kp, d.Tp)), p);
+      }
+    }
+  }
+  return RNSWINO_OK;
+}
+
+const char *rnswino_strerror(int code) {
+  switch (code) {
+    case RNSWINO_OK: return "ok";
+    case RNSWINO_E_INVALID: return "invalid argument";
+    case RNSWINO_E_UNSUPPORTED: return "unsupported configuration";
+    case RNSWINO_E_NOT_COPRIME: return "moduli are not pairwise coprime";
+    case RNSWINO_E_POINT_NOT_INVERTIBLE: return "a modulus shares a factor with an interpolation-point difference";
+    case RNSWINO_E_RANGE: return "dynamic range of the moduli set is below the worst-case output 2^14 r^2 C";
+    case RNSWINO_E_HIP: return "HIP runtime error";
+    case RNSWINO_E_NO_DEVICE: return "plan is host-only or no GPU is available";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

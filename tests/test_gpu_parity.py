@@ -1,0 +1,136 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element (bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+import paper_2007_12216_amd as rn
+from oracle import direct_conv2d
+from oracle import rnswino as rw
+
+pytestmark = pytest.mark.gpu
+
+
+def run_layer(N, C, K, H, W, r, m, pad, moduli, x, w, flags=0):
+    from paper_2007_12216_amd.layer import ConvLayer
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, flags)
+    layer.set_weights(w)
+    y = layer.forward(torch.from_numpy(x).to("cuda:0"))
+    torch.cuda.synchronize()
+    return layer, y.cpu().numpy()
+
+
+def reorder_stage(arr, t):
+    """oracle [n, xi, nu, a, b] -> [n, xi*t+nu, a, b]"""
+    n = arr.shape[0]
+    return arr.reshape(n, t * t, arr.shape[3], arr.shape[4])
+
+
+STAGE_CASES = [
+    # N, C, K, H, W, r, m, pad, moduli
+    (1, 16, 16, 16, 16, 3, 8, 1, (251, 241, 239)),           # workload 1
+    (2, 5, 7, 13, 17, 3, 8, 1, (251, 241, 239)),             # ragged tiles, odd channel counts, batch
+    (1, 70, 40, 20, 20, 3, 8, 1, (251, 241, 239, 233)),      # C spans two 64-blocks, K spans 32-row blocks raggedly
+    (1, 6, 5, 24, 24, 5, 12, 2, (251, 241, 239, 233)),       # 16x16 transform tile, 5x5 filter
+    (1, 7, 3, 28, 14, 3, 14, 1, (65521, 65519)),             # 16-bit moduli
+    (1, 4, 4, 12, 12, 3, 10, 1, (253, 251, 247)),            # the paper's running example (composite moduli)
+    (1, 4, 4, 10, 10, 3, 8, 0, (251, 241, 239)),             # no padding
+]
+
+
+@pytest.mark.parametrize("case", STAGE_CASES)
+def test_every_stage_matches_the_reference(case):
+    N, C, K, H, W, r, m, pad, moduli = case
+    print("case", case, flush=True)
+    x = si.int8_tensor(101, (N, C, H, W))
+    w = si.int8_tensor(102, (K, C, r, r))
+    layer, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    ref_y, st = rw.conv2d(x, w, m, pad, moduli, return_stages=True)
+    t = m + r - 1
+    assert np.array_equal(layer.stage(rn.STAGE_U), reorder_stage(st["U"], t)), "U"
+    assert np.array_equal(layer.stage(rn.STAGE_V), reorder_stage(st["V"], t)), "V"
+    assert np.array_equal(layer.stage(rn.STAGE_O), reorder_stage(st["O"], t)), "O"
+    assert np.array_equal(y, direct_conv2d(x, w, pad)), "y"
+    assert np.array_equal(y.astype(np.int64), ref_y)
+
+
+SHAPE_CASES = [
+    (1, 3, 64, 32, 32, 3, 8, 1, (251, 241, 239)),            # first VGG layer shape (C=3) on a small plane
+    (3, 64, 64, 24, 40, 3, 8, 1, (251, 241, 239, 233)),      # batch 3, non-square
+    (1, 130, 34, 9, 9, 3, 8, 1, (251, 241, 239, 233)),       # a single ragged tile row/column
+    (1, 1100, 16, 8, 8, 3, 8, 1, (251, 241, 239, 233)),      # C-sum longer than one accumulation span
+    (1, 48, 64, 35, 35, 5, 12, 2, (251, 241, 239, 233)),     # Inception-v3 style 5x5 x 48 x 64
+    (1, 32, 48, 28, 28, 3, 14, 1, (65521, 65519)),
+    (2, 20, 20, 11, 11, 3, 6, 1, (251, 241, 239)),           # F(6x6,3x3), odd t*t? t = 8
+    (1, 8, 8, 9, 9, 3, 7, 1, (251, 241, 239)),               # t = 9: 81 transform points, ragged group of four
+]
+
+
+@pytest.mark.parametrize("case", SHAPE_CASES)
+def test_output_is_bit_exact(case):
+    N, C, K, H, W, r, m, pad, moduli = case
+    print("case", case, flush=True)
+    x = si.int8_tensor(201, (N, C, H, W))
+    w = si.int8_tensor(202, (K, C, r, r))
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    assert np.array_equal(y, direct_conv2d(x, w, pad))
+
+
+@pytest.mark.parametrize("xv,wv", [(-128, -128), (-128, 127), (127, 127)])
+def test_extreme_values(xv, wv):
+    print("extreme", xv, wv, flush=True)
+    N, C, K, H, W, r, m, pad, moduli = 1, 96, 32, 16, 16, 3, 8, 1, (251, 241, 239, 233)
+    x = np.full((N, C, H, W), xv, dtype=np.int8)
+    w = np.full((K, C, r, r), wv, dtype=np.int8)
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    ref = direct_conv2d(x, w, pad)
+    assert np.array_equal(y, ref)
+    assert abs(int(ref[0, 0, 5, 5])) == abs(xv * wv) * 9 * C
+
+
+def test_unchecked_range_returns_the_symmetric_residue():
+    print("unchecked range", flush=True)
+    N, C, K, H, W, r, m, pad, moduli = 1, 50, 16, 8, 8, 3, 8, 1, (251, 241, 239)
+    x = np.full((N, C, H, W), -128, dtype=np.int8)
+    w = np.full((K, C, r, r), -128, dtype=np.int8)
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w, flags=rn.FLAG_ALLOW_UNCHECKED_RANGE)
+    ref = rw.sym(direct_conv2d(x, w, pad).astype(np.int64), 251 * 241 * 239)
+    assert np.array_equal(y.astype(np.int64), ref)
+    assert y[0, 0, 3, 3] == -7084549
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_workloads_full_size(idx):
+    cfg = si.layer_config(idx)
+    print("workload", idx, cfg, flush=True)
+    x, w = si.layer_tensors(cfg)
+    _, y = run_layer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["r"], cfg["m"], cfg["pad"], cfg["moduli"], x, w)
+    assert np.array_equal(y, direct_conv2d(x, w, cfg["pad"]))
+
+
+def test_determinism_and_workspace_reuse():
+    print("determinism", flush=True)
+    cfg = si.layer_config(1)
+    x, w = si.layer_tensors(cfg)
+    layer, y1 = run_layer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["r"], cfg["m"], cfg["pad"], cfg["moduli"], x, w)
+    xd = torch.from_numpy(x).to("cuda:0")
+    for _ in range(3):
+        y2 = layer.forward(xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(y1, y2.cpu().numpy())
+
+
+def test_requant_pool_matches_the_oracle_glue():
+    from oracle import requant_shift_clamp, maxpool2x2
+    print("requant", flush=True)
+    y = (si.int8_tensor(301, (2, 5, 12, 16)).astype(np.int32)) * 3001 - 777
+    yd = torch.from_numpy(y).to("cuda:0")
+    for shift, pool in ((9, False), (11, True), (0, True)):
+        shape = (2, 5, 6, 8) if pool else (2, 5, 12, 16)
+        a = torch.empty(shape, dtype=torch.int8, device="cuda:0")
+        rn.rnswino_requant_pool(yd, a, 10, 12, 16, shift, pool, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ref = requant_shift_clamp(y, shift)
+        if pool:
+            ref = maxpool2x2(ref)
+        assert np.array_equal(a.cpu().numpy(), ref)

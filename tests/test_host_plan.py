@@ -1,0 +1,120 @@
+"""Host side of the library (no GPU): symbol table, plan generator against the paper's printed
+matrices and against the oracle's independent construction, error codes."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+import paper_2007_12216_amd as rn
+from oracle import rnswino as rw
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HOST = rn.FLAG_HOST_ONLY
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "rnswino.h")).read()
+    declared = set(re.findall(r"\b(rnswino_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(rn.EXPORTED_SYMBOLS)
+    L = ctypes.CDLL(rn.library_path())
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_strerror():
+    assert rn.rnswino_strerror(0) == "ok"
+    assert "coprime" in rn.rnswino_strerror(-3)
+
+
+@pytest.mark.parametrize("moduli", [(253, 251, 247), (4001, 4331)])
+def test_generator_reproduces_the_printed_modular_matrices(paper_matrices, moduli):
+    plan = rn.rnswino_plan(1, 4, 4, 12, 12, 3, 10, 1, moduli, flags=HOST)
+    for i, p in enumerate(moduli):
+        for which, name in ((rn.MATRIX_AT, "AT"), (rn.MATRIX_G, "G"), (rn.MATRIX_BT, "BT")):
+            want = np.array([[int(v) for v in row] for row in paper_matrices[("F10_3", name, str(p))]])
+            assert np.array_equal(rn.rnswino_plan_get_matrix(plan, which, i), want), (name, p)
+
+
+@pytest.mark.parametrize("algo,m", [("F2_3", 2), ("F4_3", 4)])
+def test_small_printed_examples_modulo_a_large_prime(paper_matrices, algo, m):
+    p = 65521
+    plan = rn.rnswino_plan(1, 1, 1, 8, 8, 3, m, 1, (p, 65519), flags=HOST)
+    for which, name in ((rn.MATRIX_AT, "AT"), (rn.MATRIX_G, "G"), (rn.MATRIX_BT, "BT")):
+        want = np.array([[rw.sym(v.numerator * rw.modinv(v.denominator, p), p) for v in row]
+                         for row in paper_matrices[(algo, name, "Q")]])
+        assert np.array_equal(rn.rnswino_plan_get_matrix(plan, which, 0), want)
+
+
+@pytest.mark.parametrize("m,r,moduli", [(8, 3, (251, 241, 239, 233)), (12, 5, (251, 241, 239, 233)),
+                                        (14, 3, (65521, 65519)), (14, 3, (251, 241, 239)), (6, 3, (253, 247)),
+                                        (3, 2, (13, 17, 19, 23, 29, 31, 37, 41))])
+def test_generator_agrees_with_the_oracles_vandermonde_inversion(m, r, moduli):
+    plan = rn.rnswino_plan(1, 1, 1, 16, 16, r, m, r // 2, moduli, flags=HOST | rn.FLAG_ALLOW_UNCHECKED_RANGE)
+    for i, p in enumerate(moduli):
+        AT, G, BT = rw.matrices_mod(m, r, p)
+        assert np.array_equal(rn.rnswino_plan_get_matrix(plan, rn.MATRIX_AT, i), AT)
+        assert np.array_equal(rn.rnswino_plan_get_matrix(plan, rn.MATRIX_G, i), G)
+        assert np.array_equal(rn.rnswino_plan_get_matrix(plan, rn.MATRIX_BT, i), BT)
+    for l in range(len(moduli)):
+        for j in range(l + 1, len(moduli)):
+            assert (rn.rnswino_plan_get_mrc_inverse(plan, l, j) * moduli[l]) % moduli[j] == 1
+
+
+def test_dynamic_ranges():
+    for moduli, rng in (((253, 251, 247), 7842620), ((251, 241, 239), 7228674), ((4001, 4331), 8664165)):
+        plan = rn.rnswino_plan(1, 4, 4, 12, 12, 3, 10, 1, moduli, flags=HOST)
+        assert rn.rnswino_plan_dynamic_range(plan) == rng
+
+
+def _code(**kw):
+    args = dict(N=1, C=16, K=16, H=16, W=16, r=3, m=8, pad=1, moduli=(251, 241, 239), flags=HOST)
+    args.update(kw)
+    try:
+        rn.rnswino_plan(**args)
+    except rn.RnsWinoError as e:
+        return e.code
+    return 0
+
+
+def test_error_codes():
+    assert _code() == 0
+    assert _code(C=0) == -1 and _code(m=0) == -1 and _code(m=15) == -1          # t = 17 > 16
+    assert _code(H=1, W=1, pad=0) == -1                                          # empty output
+    assert _code(stride=2) == -2
+    assert _code(moduli=(250, 241)) == -2 and _code(moduli=(251, 65521)) == -2 and _code(moduli=(255, 241, 239)) == -2
+    assert _code(moduli=(251, 241, 241)) == -3 and _code(moduli=(249, 243, 241)) == -3
+    assert _code(moduli=()) == -1 and _code(moduli=(3, 5, 7, 11, 13, 17, 19, 23, 29)) == -1
+
+
+def test_invertibility_rule_of_section_5():
+    # 16 interpolation points: differences 11 and 13 occur, so 253 = 11*23 and 247 = 13*19 are refused ...
+    assert _code(m=14, moduli=(253, 251, 247)) == -4
+    assert _code(r=5, m=12, pad=2, moduli=(251, 247, 241, 239)) == -4
+    # ... while 12 points (the paper's running example) accept them
+    assert _code(m=10, moduli=(253, 251, 247)) == 0
+
+
+def test_range_rule():
+    # 2^14 * 9 * C against (P-1)/2 = 7 228 674 for RNS(251,241,239): C <= 49
+    assert _code(C=49) == 0 and _code(C=50) == -5
+    assert _code(C=50, flags=HOST | rn.FLAG_ALLOW_UNCHECKED_RANGE) == 0
+    assert _code(C=256, K=256, H=56, W=56) == -5                                  # the VGG layer needs 4 moduli
+    assert _code(C=256, K=256, H=56, W=56, moduli=(251, 241, 239, 233)) == 0
+    assert _code(C=512, K=512, H=28, W=28, m=14, moduli=(65521, 65519)) == 0
+
+
+def test_sizes():
+    plan = rn.rnswino_plan(1, 256, 256, 56, 56, 3, 8, 1, (251, 241, 239, 233), flags=HOST)
+    assert (plan.Ho, plan.Wo, plan.T) == (56, 56, 49)
+    assert rn.rnswino_filter_bytes(plan) == 4 * 100 * 256 * 256
+    assert rn.rnswino_workspace_bytes(plan) == 4 * 100 * 64 * 256 + 4 * 25 * 256 * 64 * 4
+
+
+def test_host_only_plan_cannot_execute():
+    plan = rn.rnswino_plan(1, 16, 16, 16, 16, 3, 8, 1, (251, 241, 239), flags=HOST)
+    buf = np.zeros(16, dtype=np.int8)
+    with pytest.raises(rn.RnsWinoError) as e:
+        rn.rnswino_conv2d(plan, buf, buf, buf, buf)
+    assert e.value.code == -7
