@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the RNS-Winograd int8 convolution hot path on one MI355X.
+
+A step is one call of rnswino_conv2d (input transform, residue GEMM, inverse transform + mixed-radix
+conversion) on the VGG16-style middle layer: N=1, C=K=256, 56x56, 3x3, pad 1, F(8x8,3x3), four 8-bit moduli.
+The filter transform is offline (section 6 of the paper) and is not timed.  Inputs are synthetic (seeded
+uniform int8) and already resident in HBM.  The metric is effective INT8 TOPS: the direct-convolution
+operation count 2*N*K*C*Ho*Wo*r^2 divided by the time per step.
+
+Timed region: each step uses its own weight/input/workspace set out of a rotation larger than the on-chip
+caches (L2 + Infinity Cache), so every step streams its operands from HBM ("cold"), as a network running
+layer after layer would.  The same loop on one buffer set ("warm") is reported beside it.
+
+One JSON line is printed: the contract fields plus
+  roofline     -- the slowest of the three kernels: algorithmic bytes per launch / its average duration, measured
+                  with HIP events recorded around each kernel on the launch stream, against 8 TB/s HBM;
+  cpu_baseline -- the direct-convolution oracle timed on this machine's host cores (context only).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ROTATION_BYTES = 640 << 20      # operands cycled through in the cold loop (> 256 MB Infinity Cache + 32 MB L2)
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime (PyTorch's events do not expose their handle portably)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.made = []
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        self.made.append(ev.value)
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        out = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(out), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return out.value
+
+    def destroy_all(self):
+        for e in self.made:
+            self.hip.hipEventDestroy(e)
+        self.made = []
+
+
+def stage_bytes(cfg, plan):
+    """Algorithmic HBM bytes per launch of each kernel: the tensors it must read and write once.
+
+    Per unit (one residue and transform point): input transform writes T*C residues, the GEMM reads K*C + T*C
+    and writes K*T, the inverse transform reads K*T; times n*t^2 units; plus x once and y (int32) once."""
+    n, t2 = len(cfg["moduli"]), plan.t * plan.t
+    N, C, K, H, W = cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"]
+    rb = 1 if max(cfg["moduli"]) < 256 else 2
+    T = plan.T
+    xb = N * C * H * W
+    vb = n * t2 * T * C * rb
+    ub = n * t2 * K * C * rb
+    ob = n * t2 * K * T * rb
+    yb = N * K * plan.Ho * plan.Wo * 4
+    return {"input_transform": xb + vb, "residue_gemm": ub + vb + ob, "inverse_transform_mrc": ob + yb}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", type=int, default=2, choices=(1, 2, 3, 4), help="single-layer workload index")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2007_12216_amd as rn
+    from paper_2007_12216_amd.layer import ConvLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K_steps, W_steps = args.steps, args.warmup
+
+    cfg = si.layer_config(args.workload)
+    x_np, w_np = si.layer_tensors(cfg)
+    layer = ConvLayer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["r"], cfg["m"], cfg["pad"], cfg["moduli"])
+    plan = layer.plan
+    layer.set_weights(w_np)
+    x0 = torch.from_numpy(x_np).to(dev)
+    ops = 2.0 * cfg["N"] * cfg["K"] * cfg["C"] * plan.Ho * plan.Wo * cfg["r"] ** 2
+
+    # ---- buffer rotation for the cold loop: every set holds its own U, x, workspace and y -------------------
+    set_bytes = layer.U.numel() + layer.workspace.numel() + x0.numel() + layer.y.numel() * 4
+    n_sets = max(2, min(64, -(-ROTATION_BYTES // set_bytes)))
+    sets = []
+    for s in range(n_sets):
+        sets.append(dict(U=layer.U.clone(), x=x0.clone(), ws=torch.empty_like(layer.workspace),
+                         y=torch.empty_like(layer.y)))
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    def step_cold(k):
+        b = sets[k % n_sets]
+        rn.rnswino_conv2d(plan, b["x"], b["U"], b["y"], b["ws"], stream)
+
+    def step_warm(k):
+        b = sets[0]
+        rn.rnswino_conv2d(plan, b["x"], b["U"], b["y"], b["ws"], stream)
+
+    def timed(step_fn):
+        for k in range(W_steps):
+            step_fn(k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K_steps):
+            step_fn(W_steps + k)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / K_steps
+
+    sec_cold = timed(step_cold)
+    sec_warm = timed(step_warm)
+
+    # ---- per-kernel durations: HIP events around each kernel, same cold rotation, same step count ----------
+    evs = HipEvents()
+    ev = [[evs.create() for _ in range(4)] for _ in range(K_steps)]
+    for k in range(W_steps):
+        step_cold(k)
+    torch.cuda.synchronize()
+    for k in range(K_steps):
+        b = sets[(W_steps + k) % n_sets]
+        rn.rnswino_conv2d_events(plan, b["x"], b["U"], b["y"], b["ws"], stream, ev[k])
+    torch.cuda.synchronize()
+    names = ("input_transform", "residue_gemm", "inverse_transform_mrc")
+    stage_ms = {nm: 0.0 for nm in names}
+    for k in range(K_steps):
+        for j, nm in enumerate(names):
+            stage_ms[nm] += evs.elapsed_ms(ev[k][j], ev[k][j + 1])
+    for nm in names:
+        stage_ms[nm] /= K_steps
+    evs.destroy_all()
+
+    bytes_per = stage_bytes(cfg, plan)
+    dominant = max(names, key=lambda nm: stage_ms[nm])
+    achieved = bytes_per[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes": bytes_per[dominant],
+                "stage_us": {nm: round(stage_ms[nm] * 1e3, 2) for nm in names},
+                "stage_GBps": {nm: round(bytes_per[nm] / (stage_ms[nm] * 1e-3) / 1e9, 1) for nm in names}}
+
+    # ---- correctness of what was timed + CPU baseline (the oracle as it stands) -----------------------------
+    torch.cuda.synchronize()
+    got = sets[(W_steps + K_steps - 1) % n_sets]["y"].cpu().numpy()
+    cpu = None
+    bit_exact = None
+    if not args.no_cpu_baseline:
+        from oracle import direct_conv2d, num_threads
+        best = float("inf")
+        ref = None
+        reps = 3 if ops < 2e10 else 1
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            ref = direct_conv2d(x_np, w_np, cfg["pad"])
+            best = min(best, time.perf_counter() - t0)
+        bit_exact = bool(np.array_equal(got, ref))
+        cpu = {"value": round(ops / best / 1e12, 6), "unit": "TOPS", "cores": num_threads(), "kind": "oracle",
+               "sample": f"whole layer ({ops / 1e9:.3f} GOP), best of {reps} runs, {best * 1e3:.1f} ms"}
+
+    out = {
+        "metric": "effective INT8 TOPS per conv layer (direct-conv ops/s)",
+        "value": round(ops / sec_cold / 1e12, 3),
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": round(sec_cold * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: N={cfg['N']} C={cfg['C']} K={cfg['K']} {cfg['H']}x{cfg['W']} "
+                               f"r={cfg['r']} pad={cfg['pad']} F({cfg['m']}x{cfg['m']},{cfg['r']}x{cfg['r']}) "
+                               f"moduli={list(cfg['moduli'])}",
+                   "direct_conv_GOP": round(ops / 1e9, 4), "cache": f"cold (rotation of {n_sets} operand sets, "
+                   f"{n_sets * set_bytes >> 20} MiB)",
+                   "warm_value_TOPS": round(ops / sec_warm / 1e12, 3), "warm_ms_per_step": round(sec_warm * 1e3, 5),
+                   "bit_exact_vs_oracle": bit_exact},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -118,6 +118,15 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
                    int32_t *y_dev, void *workspace_dev, void *stream);
 
 /*
+ * rnswino_conv2d with four caller-created hipEvent_t (passed as void*) recorded on `stream`: events[0] before
+ * the input transform, events[1] between input transform and residue GEMM, events[2] between GEMM and inverse
+ * transform, events[3] after the inverse transform + mixed-radix conversion.  For per-stage measurement
+ * (the paper's time breakdown of section 8); does not synchronise.
+ */
+int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
+                          void *workspace_dev, void *stream, void *const events[4]);
+
+/*
  * Glue for chaining layers (not part of the paper's method; the 13-layer stack workload needs it):
  *   a = clamp(floor(y / 2^shift), -128, 127), optionally followed by a 2x2 stride-2 max-pool.
  * y_dev: int32 [planes][H][W]; a_dev: int8 [planes][H][W], or [planes][H/2][W/2] when pool != 0 (H, W even).

@@ -422,8 +422,8 @@ int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, vo
   return launch_status();
 }
 
-int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
-                   void *workspace_dev, void *stream) {
+static int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
+                       void *workspace_dev, void *stream, void *const *events) {
   if (!plan || !x_dev || !U_dev || !y_dev || !workspace_dev) return RNSWINO_E_INVALID;
   if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
   const Dims &d = plan->dims;
@@ -431,17 +431,24 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
   hipStream_t st = (hipStream_t)stream;
   char *Vp = (char *)workspace_dev;
   char *Op = Vp + align256(v_bytes(d));
+  auto mark = [&](int e) {
+    if (events && events[e]) (void)hipEventRecord((hipEvent_t)events[e], st);
+  };
 
   const long long t1 = (long long)d.n * d.T * d.Cp * d.t;
   const long long t3 = (long long)d.K * d.T * d.m;
+  mark(0);
   if (d.wide) {
     hipLaunchKernelGGL(k1_input_transform_plain<int16_t>, dim3(blocks_for(t1, 256)), dim3(256), 0, st, P, x_dev, (int16_t *)Vp);
+    mark(1);
     const long long t2 = (long long)d.n * d.P2 * d.K * d.T;
     hipLaunchKernelGGL(k2_gemm_plain<int16_t>, dim3(blocks_for(t2, 256)), dim3(256), 0, st, P, (const int16_t *)U_dev,
                        (const int16_t *)Vp, (int16_t *)Op);
+    mark(2);
     hipLaunchKernelGGL(k3_inverse_mrc_plain<int16_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int16_t *)Op, y_dev);
   } else {
     hipLaunchKernelGGL(k1_input_transform_plain<int8_t>, dim3(blocks_for(t1, 256)), dim3(256), 0, st, P, x_dev, (int8_t *)Vp);
+    mark(1);
     const dim3 grid((unsigned)(d.n * d.Q), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp + 63) / 64));
     const int ncb = d.Cp / 64;
     if (ncb % 4 == 0)
@@ -450,9 +457,22 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
       hipLaunchKernelGGL(k2_gemm_i8<2>, grid, dim3(256), 0, st, P, (const int8_t *)U_dev, (const int8_t *)Vp, (uint32_t *)Op);
     else
       hipLaunchKernelGGL(k2_gemm_i8<1>, grid, dim3(256), 0, st, P, (const int8_t *)U_dev, (const int8_t *)Vp, (uint32_t *)Op);
+    mark(2);
     hipLaunchKernelGGL(k3_inverse_mrc_plain<int8_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int8_t *)Op, y_dev);
   }
+  mark(3);
   return launch_status();
+}
+
+int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
+                   void *workspace_dev, void *stream) {
+  return conv2d_impl(plan, x_dev, U_dev, y_dev, workspace_dev, stream, nullptr);
+}
+
+int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
+                          void *workspace_dev, void *stream, void *const events[4]) {
+  if (!events) return RNSWINO_E_INVALID;
+  return conv2d_impl(plan, x_dev, U_dev, y_dev, workspace_dev, stream, events);
 }
 
 int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, int32_t H, int32_t W, int32_t shift,
