@@ -15,6 +15,8 @@ struct Dims {
   int Cp, Kp, Tp;            // C padded to 64, K and T padded to 16 (tiled tensor extents)
   int P2;                    // t*t transform points
   int Q;                     // ceil(t*t / 4): groups of four transform points in the O tensor
+  int CB1, KS1;              // input transform on MFMA: 16-point column blocks ceil(t*t/16), contraction steps ceil(t/4)
+  int RB3, KS3;              // inverse transform on MFMA: 16-output row blocks ceil(m*m/16), contraction steps ceil(t*t/64)
 };
 
 // Transform matrices modulo one modulus, entries symmetric in [-(p-1)/2, (p-1)/2].
@@ -39,6 +41,9 @@ struct rnswino_plan_s {
   std::vector<rnswino::Transforms> tf;      // one per modulus
   uint32_t mrc_inv[8][8];                   // mrc_inv[l][j] = moduli[l]^-1 mod moduli[j], l < j
   int64_t dyn_range;                        // (prod - 1)/2, saturated
+  uint32_t crt_c[8];                        // prod_{l != i} m_l  mod 2^32
+  uint32_t crt_inv[8];                      // (prod_{l != i} m_l)^-1 mod m_i
+  uint32_t prod_mod32;                      // prod m_i mod 2^32
   int device;                               // HIP device the tables live on, -1 for host-only plans
   void *d_tables;                           // one device allocation holding every table below
   size_t d_tables_bytes;

@@ -167,6 +167,10 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   o.Tp = (o.T + 15) / 16 * 16;
   o.P2 = t * t;
   o.Q = (o.P2 + 3) / 4;
+  o.CB1 = (o.P2 + 15) / 16;
+  o.KS1 = (t + 3) / 4;
+  o.RB3 = (d.m * d.m + 15) / 16;
+  o.KS3 = (o.P2 + 63) / 64;
   return RNSWINO_OK;
 }
 

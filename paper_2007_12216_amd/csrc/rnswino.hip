@@ -31,6 +31,13 @@ struct KParams {
   float inv_p[8];
   int mrc_inv[8][8];          // mrc_inv[l][j] = p_l^-1 mod p_j  (l < j)
   const int32_t *AT, *G, *BT; // device tables [n][m*t], [n][t*r], [n][t*t]
+  // MFMA transforms (8-bit moduli)
+  int CB1, KS1, RB3, KS3;
+  const int8_t *KB;           // [n][CB1][KS1][64 lanes][16]: (B^T kron B^T) mod p as B-operand fragments
+  const int8_t *KA;           // [n][RB3][KS3][64 lanes][16]: (A^T kron A^T) * crt_inv mod p as A-operand fragments
+  uint32_t crt_c[8];          // prod_{l != i} p_l mod 2^32
+  double inv_pd[8];           // 1 / p_i
+  uint32_t prod_mod32;        // prod p_i mod 2^32
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -124,6 +131,190 @@ __global__ void k1_input_transform_plain(KParams P, const int8_t *__restrict__ x
     long long s = 0;
     for (int a = 0; a < t; ++a) s += (long long)BT[xi * t + a] * e[a];
     V[v_offset(i * P.P2 + xi * t + nu, tau, c, P.Tp, P.Cp)] = (RT)sym_mod64(s, p);
+  }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// K1, 8-bit moduli, on the matrix cores.  B^T d B = (B^T kron B^T) vec(d): per residue one dense
+// (t*t) x (t*t) int8 matrix applied to the t*t pixels of a tile, i.e. a GEMM whose columns are the
+// (tile, channel) pairs.  MFMA roles: A operand = pixels (rows = 16 channels of one tile), B operand =
+// the Kronecker table (columns = 16 transform points), contraction index = pixel.  A contraction step
+// of 64 covers four tile rows of 16 pixels each (lane group g = row 4s+g; columns >= t have weight 0),
+// so a lane's 16 operand bytes are 16 consecutive pixels of one image row.
+//
+// Block = 4 waves sharing one residue; each wave owns one unit = (tile, block of 64 channels).  The
+// table of the residue is staged in LDS once per block; each wave stages its 64 x t x 16 pixel patch in
+// LDS (zero outside the image), reads its operand fragments from there, and for every block of 16
+// transform points runs 4*KS1 MFMAs (four channel groups).  Accumulator rows are channels 4g+j, so
+// the four groups u give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
+// Grid: x = ceil(T * Cp/64 / 4), y = n.   Dynamic LDS: CB1*KS1 KiB + 4 * 64*4*KS1*16 B.
+// ---------------------------------------------------------------------------------------------
+template <int KS1>
+__global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const int8_t *__restrict__ x,
+                                                              int8_t *__restrict__ V) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int i = blockIdx.y;
+  const int ncb = P.Cp >> 6;
+  constexpr int ROWS = 4 * KS1;
+  const int kb_bytes = P.CB1 * KS1 * 1024;
+  const long long unit = (long long)blockIdx.x * 4 + wave;
+  const bool live = unit < (long long)P.T * ncb;
+
+  {  // table of this residue -> LDS
+    const int8_t *src = P.KB + (size_t)i * kb_bytes;
+    for (int off = threadIdx.x * 16; off < kb_bytes; off += 256 * 16) *(v4i *)(smem + off) = *(const v4i *)(src + off);
+  }
+  uint8_t *xs = smem + kb_bytes + wave * (64 * ROWS * 16);
+  int tau = 0, cb = 0;
+  if (live) {
+    tau = (int)(unit / ncb);
+    cb = (int)(unit % ncb);
+    const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+    const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
+    // columns b of the 16-pixel row segment that lie inside the image and inside the tile: [lo, hi)
+    const int lo = x0 < 0 ? -x0 : 0;
+    const int hi = min(P.t, P.W - x0);
+    uint32_t cmask[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint32_t mk = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) mk |= ((4 * d + e) >= lo && (4 * d + e) < hi) ? (0xFFu << (8 * e)) : 0u;
+      cmask[d] = mk;
+    }
+    const long long total = (long long)P.N * P.C * P.H * P.W;
+    for (int task = lane; task < 64 * ROWS; task += 64) {
+      const int c = task / ROWS, a = task - c * ROWS;
+      const int gc = cb * 64 + c, gy = y0 + a;
+      v4i val = (v4i){0, 0, 0, 0};
+      if (gc < P.C && a < P.t && gy >= 0 && gy < P.H) {
+        const long long b0 = (((long long)img * P.C + gc) * P.H + gy) * P.W + x0;
+        if (b0 >= 0 && b0 + 16 <= total) {
+          __builtin_memcpy(&val, x + b0, 16);          // one unaligned 16-byte load
+        } else {                                       // first / last bytes of the tensor
+          uint32_t wv[4] = {0, 0, 0, 0};
+          for (int b = 0; b < 16; ++b) {
+            const long long o = b0 + b;
+            if (o >= 0 && o < total) wv[b >> 2] |= (uint32_t)(uint8_t)x[o] << (8 * (b & 3));
+          }
+          val = (v4i){(int)wv[0], (int)wv[1], (int)wv[2], (int)wv[3]};
+        }
+        val[0] &= cmask[0]; val[1] &= cmask[1]; val[2] &= cmask[2]; val[3] &= cmask[3];
+      }
+      *(v4i *)(xs + task * 16) = val;
+    }
+  }
+  __syncthreads();
+  if (!live) return;
+
+  v4i af[4][KS1];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + ((16 * u + (lane & 15)) * ROWS + 4 * s + g) * 16);
+
+  const int p = P.p[i];
+  const float inv = P.inv_p[i];
+  for (int cbk = 0; cbk < P.CB1; ++cbk) {
+    v4i acc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc[u] = (v4i){0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) {
+      const v4i b = *(const v4i *)(smem + (cbk * KS1 + s) * 1024 + lane * 16);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b, acc[u], 0, 0, 0);
+    }
+    // |acc| <= t*t * 126 * 128 < 2^24
+    v4i out;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      uint32_t wv = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) wv |= ((uint32_t)mod_near(acc[u][j], inv, p) & 0xFFu) << (8 * j);
+      out[u] = (int)wv;
+    }
+    const int pt = 16 * cbk + (lane & 15);
+    if (pt < P.P2)
+      *(v4i *)(V + ((size_t)(i * P.P2 + pt) * P.Tp + tau) * P.Cp + cb * 64 + g * 16) = out;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K3, 8-bit moduli, on the matrix cores, fused with the conversion out of the RNS.
+// A^T O A = (A^T kron A^T) vec(O): per residue an (m*m) x (t*t) int8 matrix applied to the t*t transform
+// points of a (channel k, tile) pair.  MFMA roles: A operand = the Kronecker table (rows = 16 outputs),
+// B operand = O (columns = 16 consecutive tiles of one channel k), contraction index = transform point;
+// a lane's 16 operand bytes are four O words (groups q = 16s + 4g + e).
+// The table rows are pre-multiplied by (P/p_i)^-1 mod p_i, so that the accumulator w_i is the CRT
+// coefficient of residue i and  y = sum_i (P/p_i) w_i - P * rint(sum_i w_i / p_i)  (mod 2^32) is the
+// representative of the result in [-(P-1)/2, (P-1)/2]; any representative of w_i gives the same y.
+// The rounding is done in binary64: sum_i w_i/p_i = y/P + integer with |y/P| <= 1/2 - 1/(2P), and
+// the error of the sum is below 1e-14.
+// One wave = one (k, block of 16 tiles); block = 4 waves; no LDS.  Grid: ceil(K * Tp/16 / 4).
+// ---------------------------------------------------------------------------------------------
+template <int NRES, int KS3>
+__global__ __launch_bounds__(256) void k3_inverse_crt_i8(KParams P, const uint32_t *__restrict__ O,
+                                                          int32_t *__restrict__ y) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int ntb = P.Tp >> 4;
+  const long long unit = (long long)blockIdx.x * 4 + wave;
+  if (unit >= (long long)P.K * ntb) return;
+  const int k = (int)(unit / ntb), tb = (int)(unit % ntb);
+  const int tau = tb * 16 + (lane & 15);
+
+  v4i of[NRES][KS3];
+#pragma unroll
+  for (int i = 0; i < NRES; ++i)
+#pragma unroll
+    for (int s = 0; s < KS3; ++s)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int q = 16 * s + 4 * g + e;
+        of[i][s][e] = q < P.Q ? (int)O[(((size_t)i * P.Q + q) * P.Kp + k) * P.Tp + tau] : 0;
+      }
+
+  const int m = P.m, mm = m * m;
+  const bool tile_ok = tau < P.T;
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  int32_t *yplane = y + ((size_t)img * P.K + k) * P.Ho * P.Wo;
+  const float inv_m = 1.0f / (float)m;
+
+  for (int rb = 0; rb < P.RB3; ++rb) {
+    int w[NRES][4];
+#pragma unroll
+    for (int i = 0; i < NRES; ++i) {
+      v4i acc = (v4i){0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KS3; ++s) {
+        const v4i a = *(const v4i *)(P.KA + (((size_t)i * P.RB3 + rb) * KS3 + s) * 1024 + lane * 16);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, of[i][s], acc, 0, 0, 0);
+      }
+      // |acc| <= t*t * 126 * 127 < 2^24
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[i][j] = mod_near(acc[j], P.inv_p[i], P.p[i]);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t sum = 0;
+      double fs = 0.0;
+#pragma unroll
+      for (int i = 0; i < NRES; ++i) {
+        sum += P.crt_c[i] * (uint32_t)w[i][j];
+        fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
+      }
+      const int kk = __double2int_rn(fs);
+      const int val = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+      const int o = 16 * rb + 4 * g + j;
+      if (tile_ok && o < mm) {
+        const int u = (int)(((float)o + 0.5f) * inv_m);
+        const int v = o - u * m;
+        const int oy = ty * m + u, ox = tx * m + v;
+        if (oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val;
+      }
+    }
   }
 }
 
@@ -312,6 +503,14 @@ KParams make_params(const rnswino_plan_t *pl) {
   P.AT = (const int32_t *)(base + pl->off_AT);
   P.G = (const int32_t *)(base + pl->off_G);
   P.BT = (const int32_t *)(base + pl->off_BT);
+  P.CB1 = d.CB1; P.KS1 = d.KS1; P.RB3 = d.RB3; P.KS3 = d.KS3;
+  P.KB = (const int8_t *)(base + pl->off_KB);
+  P.KA = (const int8_t *)(base + pl->off_KA);
+  for (int i = 0; i < d.n; ++i) {
+    P.crt_c[i] = pl->crt_c[i];
+    P.inv_pd[i] = 1.0 / (double)pl->desc.moduli[i];
+  }
+  P.prod_mod32 = pl->prod_mod32;
   return P;
 }
 
@@ -324,6 +523,31 @@ inline size_t u_bytes(const Dims &d) { return (size_t)d.n * d.P2 * d.Kp * d.Cp *
 inline int launch_status() { return hipGetLastError() == hipSuccess ? RNSWINO_OK : RNSWINO_E_HIP; }
 
 inline unsigned blocks_for(long long total, int bs) { return (unsigned)((total + bs - 1) / bs); }
+
+template <int NRES>
+void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st) {
+  const long long units = (long long)d.K * (d.Tp / 16);
+  const dim3 grid((unsigned)((units + 3) / 4));
+  switch (d.KS3) {
+    case 1: hipLaunchKernelGGL((k3_inverse_crt_i8<NRES, 1>), grid, dim3(256), 0, st, P, O, y); break;
+    case 2: hipLaunchKernelGGL((k3_inverse_crt_i8<NRES, 2>), grid, dim3(256), 0, st, P, O, y); break;
+    case 3: hipLaunchKernelGGL((k3_inverse_crt_i8<NRES, 3>), grid, dim3(256), 0, st, P, O, y); break;
+    default: hipLaunchKernelGGL((k3_inverse_crt_i8<NRES, 4>), grid, dim3(256), 0, st, P, O, y); break;
+  }
+}
+
+void launch_k3_i8(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st) {
+  switch (d.n) {
+    case 1: launch_k3_nres<1>(d, P, O, y, st); break;
+    case 2: launch_k3_nres<2>(d, P, O, y, st); break;
+    case 3: launch_k3_nres<3>(d, P, O, y, st); break;
+    case 4: launch_k3_nres<4>(d, P, O, y, st); break;
+    case 5: launch_k3_nres<5>(d, P, O, y, st); break;
+    case 6: launch_k3_nres<6>(d, P, O, y, st); break;
+    case 7: launch_k3_nres<7>(d, P, O, y, st); break;
+    default: launch_k3_nres<8>(d, P, O, y, st); break;
+  }
+}
 
 }  // namespace
 
@@ -367,14 +591,59 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   pl->off_AT = 0;
   pl->off_G = align256(pl->off_AT + szAT);
   pl->off_BT = align256(pl->off_G + szG);
-  pl->off_KB = pl->off_KA = 0;
-  pl->d_tables_bytes = align256(pl->off_BT + szBT);
+  // CRT constants: c_i = prod_{l != i} p_l (mod 2^32), its inverse modulo p_i, and P mod 2^32
+  pl->prod_mod32 = 1;
+  for (int i = 0; i < d.n; ++i) {
+    uint32_t c32 = 1;
+    int64_t cmod = 1;
+    for (int l = 0; l < d.n; ++l)
+      if (l != i) { c32 *= desc->moduli[l]; cmod = (cmod * (int64_t)desc->moduli[l]) % (int64_t)desc->moduli[i]; }
+    pl->crt_c[i] = c32;
+    pl->crt_inv[i] = (uint32_t)mod_inverse(cmod, desc->moduli[i]);
+    pl->prod_mod32 *= desc->moduli[i];
+  }
+  const size_t szKB = d.wide ? 0 : (size_t)d.n * d.CB1 * d.KS1 * 1024;
+  const size_t szKA = d.wide ? 0 : (size_t)d.n * d.RB3 * d.KS3 * 1024;
+  pl->off_KB = align256(pl->off_BT + szBT);
+  pl->off_KA = align256(pl->off_KB + szKB);
+  pl->d_tables_bytes = align256(pl->off_KA + szKA);
   if (!(desc->flags & RNSWINO_FLAG_HOST_ONLY)) {
     std::vector<char> host(pl->d_tables_bytes, 0);
     for (int i = 0; i < d.n; ++i) {
       std::memcpy(host.data() + pl->off_AT + (size_t)i * d.m * d.t * 4, pl->tf[i].AT.data(), (size_t)d.m * d.t * 4);
       std::memcpy(host.data() + pl->off_G + (size_t)i * d.t * d.r * 4, pl->tf[i].G.data(), (size_t)d.t * d.r * 4);
       std::memcpy(host.data() + pl->off_BT + (size_t)i * d.t * d.t * 4, pl->tf[i].BT.data(), (size_t)d.t * d.t * 4);
+    }
+    if (!d.wide) {
+      // Kronecker tables in MFMA fragment order: lane = (row or column % 16) + 16*g, 16 bytes per lane
+      for (int i = 0; i < d.n; ++i) {
+        const int64_t p = desc->moduli[i];
+        const std::vector<int32_t> &BT = pl->tf[i].BT, &AT = pl->tf[i].AT;
+        int8_t *kb = (int8_t *)host.data() + pl->off_KB + (size_t)i * d.CB1 * d.KS1 * 1024;
+        for (int cbk = 0; cbk < d.CB1; ++cbk)
+          for (int s = 0; s < d.KS1; ++s)
+            for (int lane = 0; lane < 64; ++lane)
+              for (int b = 0; b < 16; ++b) {
+                const int pt = 16 * cbk + (lane & 15), a = 4 * s + (lane >> 4);
+                int32_t v = 0;
+                if (pt < d.P2 && a < d.t && b < d.t)
+                  v = sym_residue((int64_t)BT[(size_t)(pt / d.t) * d.t + a] * BT[(size_t)(pt % d.t) * d.t + b], p);
+                kb[((size_t)(cbk * d.KS1 + s) * 64 + lane) * 16 + b] = (int8_t)v;
+              }
+        int8_t *ka = (int8_t *)host.data() + pl->off_KA + (size_t)i * d.RB3 * d.KS3 * 1024;
+        for (int rb = 0; rb < d.RB3; ++rb)
+          for (int s = 0; s < d.KS3; ++s)
+            for (int lane = 0; lane < 64; ++lane)
+              for (int b = 0; b < 16; ++b) {
+                const int o = 16 * rb + (lane & 15), pt = 64 * s + 16 * (lane >> 4) + b;
+                int32_t v = 0;
+                if (o < d.m * d.m && pt < d.P2) {
+                  const int64_t aa = (int64_t)AT[(size_t)(o / d.m) * d.t + pt / d.t] * AT[(size_t)(o % d.m) * d.t + pt % d.t];
+                  v = sym_residue((aa % p) * (int64_t)pl->crt_inv[i], p);
+                }
+                ka[((size_t)(rb * d.KS3 + s) * 64 + lane) * 16 + b] = (int8_t)v;
+              }
+      }
     }
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); delete pl; return RNSWINO_E_NO_DEVICE; }
@@ -383,6 +652,18 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
       (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP;
     }
     pl->device = dev;
+    if (!d.wide) {
+      // the input-transform kernel keeps its table and four pixel patches in LDS: up to 128 KiB of the 160 KiB
+      const int lds = d.CB1 * d.KS1 * 1024 + 4 * 64 * 4 * d.KS1 * 16;
+      hipError_t e = hipSuccess;
+      switch (d.KS1) {
+        case 1: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
+        case 2: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
+        case 3: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<3>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
+        default: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<4>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
+      }
+      if (e != hipSuccess) { (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP; }
+    }
   }
   *out = pl;
   return RNSWINO_OK;
@@ -447,7 +728,17 @@ static int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const vo
     mark(2);
     hipLaunchKernelGGL(k3_inverse_mrc_plain<int16_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int16_t *)Op, y_dev);
   } else {
-    hipLaunchKernelGGL(k1_input_transform_plain<int8_t>, dim3(blocks_for(t1, 256)), dim3(256), 0, st, P, x_dev, (int8_t *)Vp);
+    {
+      const long long units = (long long)d.T * (d.Cp / 64);
+      const dim3 g1((unsigned)((units + 3) / 4), (unsigned)d.n);
+      const size_t lds = (size_t)d.CB1 * d.KS1 * 1024 + (size_t)4 * 64 * 4 * d.KS1 * 16;
+      switch (d.KS1) {
+        case 1: hipLaunchKernelGGL(k1_input_transform_i8<1>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
+        case 2: hipLaunchKernelGGL(k1_input_transform_i8<2>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
+        case 3: hipLaunchKernelGGL(k1_input_transform_i8<3>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
+        default: hipLaunchKernelGGL(k1_input_transform_i8<4>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
+      }
+    }
     mark(1);
     const dim3 grid((unsigned)(d.n * d.Q), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp + 63) / 64));
     const int ncb = d.Cp / 64;
@@ -458,7 +749,7 @@ static int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const vo
     else
       hipLaunchKernelGGL(k2_gemm_i8<1>, grid, dim3(256), 0, st, P, (const int8_t *)U_dev, (const int8_t *)Vp, (uint32_t *)Op);
     mark(2);
-    hipLaunchKernelGGL(k3_inverse_mrc_plain<int8_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int8_t *)Op, y_dev);
+    launch_k3_i8(d, P, (const uint32_t *)Op, y_dev, st);
   }
   mark(3);
   return launch_status();
