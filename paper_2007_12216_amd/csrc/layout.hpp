@@ -14,7 +14,7 @@
 // 4*g + j, and four accumulators u = b/4 cover the 64 channels).
 //
 //   U  [n][t*t][Kp/16][Cp/64][lane = (k%16) + 16*g][16 B]      (fragment-major: a wave reads 1 KiB runs)
-//   V  [n][t*t][Tp][Cp/64][g][16 B]                            (tile-major rows of Cp bytes)
+//   V  [n][t*t][Tp/16][Cp/64][tile%16][g][16 B]                 (fragment-major: 1 KiB per 16 tiles x 64 channels)
 //   O  [n][Q][Kp][Tp][4 B]      byte e of the last axis is transform point 4*q + e
 //
 // n moduli, t*t transform points, Cp = C rounded up to 64 (padding channels are
@@ -48,7 +48,8 @@ RNSW_HD size_t u_offset(int slab, int k, int c, int Kp, int Cp) {
 }
 
 RNSW_HD size_t v_offset(int slab, int tau, int c, int Tp, int Cp) {
-  return ((size_t)slab * Tp + tau) * Cp + (size_t)(c >> 6) * 64 + chan_pos64(c & 63);
+  const size_t frag = ((size_t)slab * (Tp >> 4) + (tau >> 4)) * (Cp >> 6) + (c >> 6);
+  return frag * 1024 + (size_t)((tau & 15) * 64 + chan_pos64(c & 63));
 }
 
 RNSW_HD size_t o_offset(int i, int pt, int k, int tau, int Q, int Kp, int Tp) {

@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
     }
     const int pt = 16 * cbk + (lane & 15);
     if (pt < P.P2)
-      *(v4i *)(V + ((size_t)(i * P.P2 + pt) * P.Tp + tau) * P.Cp + cb * 64 + g * 16) = out;
+      *(v4i *)(V + (((size_t)(i * P.P2 + pt) * (P.Tp >> 4) + (tau >> 4)) * ncb + cb) * 1024 + (tau & 15) * 64 + g * 16) = out;
   }
 }
 
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(256) void k2_gemm_i8(KParams P, const int8_t *__res
   if (pt < P.P2) {
     const int slab = i * P.P2 + pt;
     const int8_t *Ub = U + (size_t)slab * nkb * ncb * 1024 + lane * 16;
-    const int8_t *Vb = V + (size_t)slab * P.Tp * P.Cp + (size_t)(lane & 15) * P.Cp + (lane >> 4) * 16;
+    const int8_t *Vb = V + (size_t)slab * ntb * ncb * 1024 + (lane & 15) * 64 + (lane >> 4) * 16;
     for (int s0 = 0; s0 < ncb; s0 += KS) {
       v4i a[KS][2], b[KS][4];
 #pragma unroll
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void k2_gemm_i8(KParams P, const int8_t *__res
 #pragma unroll
         for (int tb = 0; tb < 4; ++tb) {
           b[s][tb] = (v4i){0, 0, 0, 0};
-          if (tb0 + tb < ntb) b[s][tb] = *(const v4i *)(Vb + (size_t)(tb0 + tb) * 16 * P.Cp + (s0 + s) * 64);
+          if (tb0 + tb < ntb) b[s][tb] = *(const v4i *)(Vb + ((size_t)(tb0 + tb) * ncb + s0 + s) * 1024);
         }
       }
 #pragma unroll
