@@ -141,38 +141,42 @@ __global__ void k1_input_transform_plain(KParams P, const int8_t *__restrict__ x
 // (tile, channel) pairs.  MFMA roles: A operand = pixels (rows = 16 channels of one tile), B operand =
 // the Kronecker table (columns = 16 transform points), contraction index = pixel.  A contraction step
 // of 64 covers four tile rows of 16 pixels each (lane group g = row 4s+g; columns >= t have weight 0),
-// so a lane's 16 operand bytes are 16 consecutive pixels of one image row.
+// so a lane's 16 operand bytes are 16 consecutive pixels of one image row: one unaligned 16-byte load,
+// masked where the tile hangs over the image border.
 //
-// Block = 4 waves sharing one residue; each wave owns one unit = (tile, block of 64 channels).  The
-// table of the residue is staged in LDS once per block; each wave stages its 64 x t x 16 pixel patch in
-// LDS (zero outside the image), reads its operand fragments from there, and for every block of 16
-// transform points runs 4*KS1 MFMAs (four channel groups).  Accumulator rows are channels 4g+j, so
-// the four groups u give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
-// Grid: x = ceil(T * Cp/64 / 4), y = n.   Dynamic LDS: CB1*KS1 KiB + 4 * 64*4*KS1*16 B.
+// Block = (tile, block of 64 channels, residue): its 64 x t x 16 pixel patch is gathered once into LDS
+// (the gather of 16-byte row segments is what costs; sharing it between the four waves pays), then each
+// wave takes every fourth group of K1_CPW column blocks.  Accumulator rows are channels 4g+j, so the four
+// channel groups u give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
+// Grid: x = T * Cp/64, y = n; 256 threads; 64 * 4*KS1 * 16 bytes of LDS.
 // ---------------------------------------------------------------------------------------------
+constexpr int K1_CPW = 2;
+
+// low byte of the residue of x (|x| < 2^24): the mantissa trick of mod_near with the constant term dropped,
+// because 2^22 * p is a multiple of 256
+__device__ __forceinline__ uint32_t mod_lowbyte(int x, float inv_p, int neg_p) {
+  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
+  return (uint32_t)(__mul24(__float_as_int(f), neg_p) + x);
+}
+
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);
+  const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+  return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
+}
+
 template <int KS1>
 __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const int8_t *__restrict__ x,
                                                               int8_t *__restrict__ V) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
-  const int i = blockIdx.y;
-  const int ncb = P.Cp >> 6;
   constexpr int ROWS = 4 * KS1;
-  const int kb_bytes = P.CB1 * KS1 * 1024;
-  const long long unit = (long long)blockIdx.x * 4 + wave;
-  const bool live = unit < (long long)P.T * ncb;
-
-  {  // table of this residue -> LDS
-    const int8_t *src = P.KB + (size_t)i * kb_bytes;
-    for (int off = threadIdx.x * 16; off < kb_bytes; off += 256 * 16) *(v4i *)(smem + off) = *(const v4i *)(src + off);
-  }
-  uint8_t *xs = smem + kb_bytes + wave * (64 * ROWS * 16);
-  int tau = 0, cb = 0;
-  if (live) {
-    tau = (int)(unit / ncb);
-    cb = (int)(unit % ncb);
-    const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
-    const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
+  __shared__ __attribute__((aligned(16))) uint8_t xs[64 * ROWS * 16];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int ncb = P.Cp >> 6;
+  const int i = blockIdx.y;
+  const int cb = blockIdx.x % ncb, tau = blockIdx.x / ncb;
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
+  {
     // columns b of the 16-pixel row segment that lie inside the image and inside the tile: [lo, hi)
     const int lo = x0 < 0 ? -x0 : 0;
     const int hi = min(P.t, P.W - x0);
@@ -185,7 +189,7 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
       cmask[d] = mk;
     }
     const long long total = (long long)P.N * P.C * P.H * P.W;
-    for (int task = lane; task < 64 * ROWS; task += 64) {
+    for (int task = threadIdx.x; task < 64 * ROWS; task += 256) {
       const int c = task / ROWS, a = task - c * ROWS;
       const int gc = cb * 64 + c, gy = y0 + a;
       v4i val = (v4i){0, 0, 0, 0};
@@ -207,7 +211,6 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
     }
   }
   __syncthreads();
-  if (!live) return;
 
   v4i af[4][KS1];
 #pragma unroll
@@ -215,30 +218,33 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
 #pragma unroll
     for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + ((16 * u + (lane & 15)) * ROWS + 4 * s + g) * 16);
 
-  const int p = P.p[i];
+  const int neg_p = -P.p[i];
   const float inv = P.inv_p[i];
-  for (int cbk = 0; cbk < P.CB1; ++cbk) {
-    v4i acc[4];
+  const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
+  for (int cg = wave; cg < ncg; cg += 4) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) acc[u] = (v4i){0, 0, 0, 0};
+    for (int cc = 0; cc < K1_CPW; ++cc) {
+      const int cbk = cg * K1_CPW + cc;
+      if (cbk >= P.CB1) break;
+      v4i acc[4];
 #pragma unroll
-    for (int s = 0; s < KS1; ++s) {
-      const v4i b = *(const v4i *)(smem + (cbk * KS1 + s) * 1024 + lane * 16);
+      for (int u = 0; u < 4; ++u) acc[u] = (v4i){0, 0, 0, 0};
 #pragma unroll
-      for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b, acc[u], 0, 0, 0);
+      for (int s = 0; s < KS1; ++s) {
+        const v4i b = *(const v4i *)(P.KB + (((size_t)i * P.CB1 + cbk) * KS1 + s) * 1024 + lane * 16);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b, acc[u], 0, 0, 0);
+      }
+      // |acc| <= t*t * 126 * 128 < 2^24
+      v4i out;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        out[u] = (int)pack_low_bytes(mod_lowbyte(acc[u][0], inv, neg_p), mod_lowbyte(acc[u][1], inv, neg_p),
+                                     mod_lowbyte(acc[u][2], inv, neg_p), mod_lowbyte(acc[u][3], inv, neg_p));
+      const int pt = 16 * cbk + (lane & 15);
+      if (pt < P.P2)
+        *(v4i *)(V + (((size_t)(i * P.P2 + pt) * (P.Tp >> 4) + (tau >> 4)) * ncb + cb) * 1024 + (tau & 15) * 64 + g * 16) = out;
     }
-    // |acc| <= t*t * 126 * 128 < 2^24
-    v4i out;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      uint32_t wv = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) wv |= ((uint32_t)mod_near(acc[u][j], inv, p) & 0xFFu) << (8 * j);
-      out[u] = (int)wv;
-    }
-    const int pt = 16 * cbk + (lane & 15);
-    if (pt < P.P2)
-      *(v4i *)(V + (((size_t)(i * P.P2 + pt) * (P.Tp >> 4) + (tau >> 4)) * ncb + cb) * 1024 + (tau & 15) * 64 + g * 16) = out;
   }
 }
 
@@ -652,18 +658,6 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
       (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP;
     }
     pl->device = dev;
-    if (!d.wide) {
-      // the input-transform kernel keeps its table and four pixel patches in LDS: up to 128 KiB of the 160 KiB
-      const int lds = d.CB1 * d.KS1 * 1024 + 4 * 64 * 4 * d.KS1 * 16;
-      hipError_t e = hipSuccess;
-      switch (d.KS1) {
-        case 1: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
-        case 2: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
-        case 3: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<3>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
-        default: e = hipFuncSetAttribute((const void *)k1_input_transform_i8<4>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); break;
-      }
-      if (e != hipSuccess) { (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP; }
-    }
   }
   *out = pl;
   return RNSWINO_OK;
@@ -729,14 +723,12 @@ static int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const vo
     hipLaunchKernelGGL(k3_inverse_mrc_plain<int16_t>, dim3(blocks_for(t3, 256)), dim3(256), 0, st, P, (const int16_t *)Op, y_dev);
   } else {
     {
-      const long long units = (long long)d.T * (d.Cp / 64);
-      const dim3 g1((unsigned)((units + 3) / 4), (unsigned)d.n);
-      const size_t lds = (size_t)d.CB1 * d.KS1 * 1024 + (size_t)4 * 64 * 4 * d.KS1 * 16;
+      const dim3 g1((unsigned)(d.T * (d.Cp / 64)), (unsigned)d.n);
       switch (d.KS1) {
-        case 1: hipLaunchKernelGGL(k1_input_transform_i8<1>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
-        case 2: hipLaunchKernelGGL(k1_input_transform_i8<2>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
-        case 3: hipLaunchKernelGGL(k1_input_transform_i8<3>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
-        default: hipLaunchKernelGGL(k1_input_transform_i8<4>, g1, dim3(256), lds, st, P, x_dev, (int8_t *)Vp); break;
+        case 1: hipLaunchKernelGGL(k1_input_transform_i8<1>, g1, dim3(256), 0, st, P, x_dev, (int8_t *)Vp); break;
+        case 2: hipLaunchKernelGGL(k1_input_transform_i8<2>, g1, dim3(256), 0, st, P, x_dev, (int8_t *)Vp); break;
+        case 3: hipLaunchKernelGGL(k1_input_transform_i8<3>, g1, dim3(256), 0, st, P, x_dev, (int8_t *)Vp); break;
+        default: hipLaunchKernelGGL(k1_input_transform_i8<4>, g1, dim3(256), 0, st, P, x_dev, (int8_t *)Vp); break;
       }
     }
     mark(1);
