@@ -42,6 +42,7 @@ struct rnswino_plan_s {
   uint32_t mrc_inv[8][8];                   // mrc_inv[l][j] = moduli[l]^-1 mod moduli[j], l < j
   int64_t dyn_range;                        // (prod - 1)/2, saturated
   uint32_t crt_c[8];                        // prod_{l != i} m_l  mod 2^32
+  int crt_c_exact_small[8];                 // 1 when prod_{l != i} m_l itself is below 2^24
   uint32_t crt_inv[8];                      // (prod_{l != i} m_l)^-1 mod m_i
   uint32_t prod_mod32;                      // prod m_i mod 2^32
   int device;                               // HIP device the tables live on, -1 for host-only plans

@@ -38,6 +38,7 @@ struct KParams {
   uint32_t crt_c[8];          // prod_{l != i} p_l mod 2^32
   double inv_pd[8];           // 1 / p_i
   uint32_t prod_mod32;        // prod p_i mod 2^32
+  int crt24;                  // every crt_c[i] < 2^24: 24-bit multiplies suffice
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -61,6 +62,19 @@ __device__ __forceinline__ int mod_near(int x, float inv_p, int p) {
   const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
   const int q = __float_as_int(f) - 0x4B400000;
   return x - __mul24(q, p);
+}
+
+// low byte of the residue of x (|x| < 2^24): the mantissa trick of mod_near with the constant term dropped,
+// because 2^22 * p is a multiple of 256
+__device__ __forceinline__ uint32_t mod_lowbyte(int x, float inv_p, int neg_p) {
+  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
+  return (uint32_t)(__mul24(__float_as_int(f), neg_p) + x);
+}
+
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);
+  const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+  return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -152,19 +166,6 @@ __global__ void k1_input_transform_plain(KParams P, const int8_t *__restrict__ x
 // ---------------------------------------------------------------------------------------------
 constexpr int K1_CPW = 2;
 
-// low byte of the residue of x (|x| < 2^24): the mantissa trick of mod_near with the constant term dropped,
-// because 2^22 * p is a multiple of 256
-__device__ __forceinline__ uint32_t mod_lowbyte(int x, float inv_p, int neg_p) {
-  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
-  return (uint32_t)(__mul24(__float_as_int(f), neg_p) + x);
-}
-
-__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
-  const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);
-  const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
-  return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
-}
-
 template <int KS1>
 __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const int8_t *__restrict__ x,
                                                               int8_t *__restrict__ V) {
@@ -210,6 +211,17 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
       *(v4i *)(xs + task * 16) = val;
     }
   }
+  // table fragments of this wave's first column-block group: issued before the barrier so that their latency
+  // overlaps the gather
+  const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
+  v4i bf[K1_CPW][KS1];
+#pragma unroll
+  for (int cc = 0; cc < K1_CPW; ++cc)
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) {
+      const int cbk = min(wave * K1_CPW + cc, P.CB1 - 1);
+      bf[cc][s] = *(const v4i *)(P.KB + (((size_t)i * P.CB1 + cbk) * KS1 + s) * 1024 + lane * 16);
+    }
   __syncthreads();
 
   v4i af[4][KS1];
@@ -220,8 +232,16 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
 
   const int neg_p = -P.p[i];
   const float inv = P.inv_p[i];
-  const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
   for (int cg = wave; cg < ncg; cg += 4) {
+    if (cg != wave) {
+#pragma unroll
+      for (int cc = 0; cc < K1_CPW; ++cc)
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) {
+          const int cbk = min(cg * K1_CPW + cc, P.CB1 - 1);
+          bf[cc][s] = *(const v4i *)(P.KB + (((size_t)i * P.CB1 + cbk) * KS1 + s) * 1024 + lane * 16);
+        }
+    }
 #pragma unroll
     for (int cc = 0; cc < K1_CPW; ++cc) {
       const int cbk = cg * K1_CPW + cc;
@@ -231,9 +251,8 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
       for (int u = 0; u < 4; ++u) acc[u] = (v4i){0, 0, 0, 0};
 #pragma unroll
       for (int s = 0; s < KS1; ++s) {
-        const v4i b = *(const v4i *)(P.KB + (((size_t)i * P.CB1 + cbk) * KS1 + s) * 1024 + lane * 16);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b, acc[u], 0, 0, 0);
+        for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], bf[cc][s], acc[u], 0, 0, 0);
       }
       // |acc| <= t*t * 126 * 128 < 2^24
       v4i out;
@@ -259,16 +278,17 @@ __global__ __launch_bounds__(256) void k1_input_transform_i8(KParams P, const in
 // representative of the result in [-(P-1)/2, (P-1)/2]; any representative of w_i gives the same y.
 // The rounding is done in binary64: sum_i w_i/p_i = y/P + integer with |y/P| <= 1/2 - 1/(2P), and
 // the error of the sum is below 1e-14.
-// One wave = one (k, block of 16 tiles); block = 4 waves; no LDS.  Grid: ceil(K * Tp/16 / 4).
+// Block = one (k, block of 16 tiles); its waves take the 16-output row blocks rb = wave, wave+4, ...
+// (four waves cover an 8x8 output tile); every wave loads the O operand itself (the copies hit in L1).
+// No LDS.  Grid: K * Tp/16 blocks of 256 threads.
 // ---------------------------------------------------------------------------------------------
 template <int NRES, int KS3>
 __global__ __launch_bounds__(256) void k3_inverse_crt_i8(KParams P, const uint32_t *__restrict__ O,
                                                           int32_t *__restrict__ y) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  if (wave >= P.RB3) return;
   const int ntb = P.Tp >> 4;
-  const long long unit = (long long)blockIdx.x * 4 + wave;
-  if (unit >= (long long)P.K * ntb) return;
-  const int k = (int)(unit / ntb), tb = (int)(unit % ntb);
+  const int k = blockIdx.x / ntb, tb = blockIdx.x % ntb;
   const int tau = tb * 16 + (lane & 15);
 
   v4i of[NRES][KS3];
@@ -279,7 +299,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_i8(KParams P, const uint32
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int q = 16 * s + 4 * g + e;
-        of[i][s][e] = q < P.Q ? (int)O[(((size_t)i * P.Q + q) * P.Kp + k) * P.Tp + tau] : 0;
+        of[i][s][e] = (q < P.Q && tau < P.T) ? (int)O[(((size_t)i * P.Q + q) * P.Kp + k) * P.Tp + tau] : 0;
       }
 
   const int m = P.m, mm = m * m;
@@ -287,9 +307,10 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_i8(KParams P, const uint32
   const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
   int32_t *yplane = y + ((size_t)img * P.K + k) * P.Ho * P.Wo;
   const float inv_m = 1.0f / (float)m;
+  const bool vec4 = ((m & 3) == 0) && ((P.Wo & 3) == 0);   // four consecutive outputs stay in one row, 16-byte aligned
 
-  for (int rb = 0; rb < P.RB3; ++rb) {
-    int w[NRES][4];
+  for (int rb = wave; rb < P.RB3; rb += 4) {
+    uint32_t w[NRES][4];
 #pragma unroll
     for (int i = 0; i < NRES; ++i) {
       v4i acc = (v4i){0, 0, 0, 0};
@@ -298,27 +319,38 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_i8(KParams P, const uint32
         const v4i a = *(const v4i *)(P.KA + (((size_t)i * P.RB3 + rb) * KS3 + s) * 1024 + lane * 16);
         acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, of[i][s], acc, 0, 0, 0);
       }
-      // |acc| <= t*t * 126 * 127 < 2^24
+      // |acc| <= t*t * 126 * 127 < 2^24; residue shifted by +p so that it is non-negative (0 <= w < 2p + 2)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) w[i][j] = mod_near(acc[j], P.inv_p[i], P.p[i]);
+      for (int j = 0; j < 4; ++j) w[i][j] = (uint32_t)(mod_near(acc[j], P.inv_p[i], P.p[i]) + P.p[i]);
     }
+    int val[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       uint32_t sum = 0;
       double fs = 0.0;
 #pragma unroll
       for (int i = 0; i < NRES; ++i) {
-        sum += P.crt_c[i] * (uint32_t)w[i][j];
+        sum += P.crt24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
         fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
       }
       const int kk = __double2int_rn(fs);
-      const int val = (int)(sum - P.prod_mod32 * (uint32_t)kk);
-      const int o = 16 * rb + 4 * g + j;
-      if (tile_ok && o < mm) {
+      val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+    }
+    const int o0 = 16 * rb + 4 * g;
+    if (!tile_ok || o0 >= mm) continue;
+    if (vec4) {
+      const int u = (int)(((float)o0 + 0.5f) * inv_m);
+      const int v = o0 - u * m;
+      const int oy = ty * m + u, ox = tx * m + v;
+      if (oy < P.Ho && ox < P.Wo) *(v4i *)(yplane + (size_t)oy * P.Wo + ox) = (v4i){val[0], val[1], val[2], val[3]};
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int o = o0 + j;
         const int u = (int)(((float)o + 0.5f) * inv_m);
         const int v = o - u * m;
         const int oy = ty * m + u, ox = tx * m + v;
-        if (oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val;
+        if (o < mm && oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val[j];
       }
     }
   }
@@ -395,7 +427,7 @@ __global__ __launch_bounds__(256) void k2_gemm_i8(KParams P, const int8_t *__res
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int row = rm * 16 + 4 * (lane >> 4) + j, col = tb * 16 + (lane & 15);
-        tile8[(row * 64 + col) * 4 + wave] = (uint8_t)mod_near(acc[rm][tb][j], inv, p);
+        tile8[(row * 64 + col) * 4 + wave] = (uint8_t)mod_lowbyte(acc[rm][tb][j], inv, -p);
       }
   __syncthreads();
   uint32_t *Ob = O + ((size_t)i * P.Q + q) * P.Kp * P.Tp;
@@ -404,7 +436,7 @@ __global__ __launch_bounds__(256) void k2_gemm_i8(KParams P, const int8_t *__res
     const int e = it * 256 + threadIdx.x;
     const int row = e >> 6, col = e & 63;
     const int k = kb0 * 16 + row, tau = tb0 * 16 + col;
-    if (k < P.Kp && tau < P.Tp) Ob[(size_t)k * P.Tp + tau] = tile[e];
+    if (k < P.Kp && tau < P.T) Ob[(size_t)k * P.Tp + tau] = tile[e];   // padding tiles are neither written nor read
   }
 }
 
@@ -517,6 +549,9 @@ KParams make_params(const rnswino_plan_t *pl) {
     P.inv_pd[i] = 1.0 / (double)pl->desc.moduli[i];
   }
   P.prod_mod32 = pl->prod_mod32;
+  P.crt24 = 1;
+  for (int i = 0; i < d.n; ++i)
+    if (pl->crt_c_exact_small[i] == 0) P.crt24 = 0;
   return P;
 }
 
@@ -532,8 +567,7 @@ inline unsigned blocks_for(long long total, int bs) { return (unsigned)((total +
 
 template <int NRES>
 void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st) {
-  const long long units = (long long)d.K * (d.Tp / 16);
-  const dim3 grid((unsigned)((units + 3) / 4));
+  const dim3 grid((unsigned)(d.K * (d.Tp / 16)));
   switch (d.KS3) {
     case 1: hipLaunchKernelGGL((k3_inverse_crt_i8<NRES, 1>), grid, dim3(256), 0, st, P, O, y); break;
     case 2: hipLaunchKernelGGL((k3_inverse_crt_i8<NRES, 2>), grid, dim3(256), 0, st, P, O, y); break;
@@ -605,6 +639,12 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
     for (int l = 0; l < d.n; ++l)
       if (l != i) { c32 *= desc->moduli[l]; cmod = (cmod * (int64_t)desc->moduli[l]) % (int64_t)desc->moduli[i]; }
     pl->crt_c[i] = c32;
+    {
+      unsigned __int128 full = 1;
+      for (int l = 0; l < d.n; ++l)
+        if (l != i) { full *= desc->moduli[l]; if (full > ((unsigned __int128)1 << 40)) full = (unsigned __int128)1 << 40; }
+      pl->crt_c_exact_small[i] = full < ((unsigned __int128)1 << 24) ? 1 : 0;
+    }
     pl->crt_inv[i] = (uint32_t)mod_inverse(cmod, desc->moduli[i]);
     pl->prod_mod32 *= desc->moduli[i];
   }
