@@ -1,0 +1,160 @@
+// K1: input transform on the matrix cores.
+//
+// V[i][xi,nu][tau][c] = (B^T_p d B_p)[xi,nu] mod p_i for every tile tau and channel c (paper section 6: shared
+// by all K filters).  B^T d B = (B^T kron B^T) vec(d): per residue one dense (t*t) x (t*t) matrix applied to the
+// t*t pixels of a tile, i.e. a GEMM whose columns are the (tile, channel) pairs.  MFMA roles
+// (v_mfma_i32_16x16x64_i8): A operand = pixels (rows = 16 channels of one tile), B operand = the Kronecker
+// table (columns = 16 transform points), contraction index = pixel.  A contraction step of 64 covers four tile
+// rows of 16 pixels each (lane group g = row 4s+g; columns >= t have weight 0), so a lane's 16 operand bytes are
+// 16 consecutive pixels of one image row: one unaligned 16-byte load, masked where the tile hangs over the
+// image border (zero padding and ragged last tiles).
+//
+// Block = (tile, block of 64 channels, residue): its 64 x t x 16 pixel patch is gathered once into LDS (the
+// gather of 16-byte row segments is what costs; sharing it between the four waves pays), then each wave takes
+// every fourth group of K1_CPW column blocks.  Accumulator rows are channels 4g+j, so the four channel groups u
+// give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
+// 16-bit moduli: the table has a high and a low byte plane, V = (256 * sum_h + sum_l) mod p, stored as two planes.
+// Grid: x = T * Cp/64, y = n; 256 threads; 64 * 4*KS1 * 16 bytes of LDS.
+#pragma once
+#include "kernels_common.hpp"
+
+namespace rnswino {
+
+constexpr int K1_CPW = 2;
+
+template <int KS1, bool WIDE>
+__global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_t *__restrict__ x,
+                                                           int8_t *__restrict__ V) {
+  constexpr int ROWS = 4 * KS1;
+  constexpr int PL = WIDE ? 2 : 1;
+  __shared__ __attribute__((aligned(16))) uint8_t xs[64 * ROWS * 16];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int ncb = P.Cp >> 6;
+  const int i = blockIdx.y;
+  const int cb = blockIdx.x % ncb, tau = blockIdx.x / ncb;
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
+  {
+    // columns b of the 16-pixel row segment that lie inside the image and inside the tile: [lo, hi)
+    const int lo = x0 < 0 ? -x0 : 0;
+    const int hi = min(P.t, P.W - x0);
+    uint32_t cmask[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint32_t mk = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) mk |= ((4 * d + e) >= lo && (4 * d + e) < hi) ? (0xFFu << (8 * e)) : 0u;
+      cmask[d] = mk;
+    }
+    const long long total = (long long)P.N * P.C * P.H * P.W;
+    for (int task = threadIdx.x; task < 64 * ROWS; task += 256) {
+      const int c = task / ROWS, a = task - c * ROWS;
+      const int gc = cb * 64 + c, gy = y0 + a;
+      v4i val = (v4i){0, 0, 0, 0};
+      if (gc < P.C && a < P.t && gy >= 0 && gy < P.H) {
+        const long long b0 = (((long long)img * P.C + gc) * P.H + gy) * P.W + x0;
+        if (b0 >= 0 && b0 + 16 <= total) {
+          __builtin_memcpy(&val, x + b0, 16);          // one unaligned 16-byte load
+        } else {                                       // first / last bytes of the tensor
+          uint32_t wv[4] = {0, 0, 0, 0};
+          for (int b = 0; b < 16; ++b) {
+            const long long o = b0 + b;
+            if (o >= 0 && o < total) wv[b >> 2] |= (uint32_t)(uint8_t)x[o] << (8 * (b & 3));
+          }
+          val = (v4i){(int)wv[0], (int)wv[1], (int)wv[2], (int)wv[3]};
+        }
+        val[0] &= cmask[0]; val[1] &= cmask[1]; val[2] &= cmask[2]; val[3] &= cmask[3];
+      }
+      *(v4i *)(xs + task * 16) = val;
+    }
+  }
+  // table fragments of this wave's first column-block group: issued before the barrier so that their latency
+  // overlaps the gather
+  const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
+  const int8_t *KBi = P.KB + (size_t)i * P.CB1 * KS1 * PL * 1024 + lane * 16;
+  v4i bf[K1_CPW][KS1][PL];
+#pragma unroll
+  for (int cc = 0; cc < K1_CPW; ++cc)
+#pragma unroll
+    for (int s = 0; s < KS1; ++s)
+#pragma unroll
+      for (int pl = 0; pl < PL; ++pl) {
+        const int cbk = min(wave * K1_CPW + cc, P.CB1 - 1);
+        bf[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
+      }
+  __syncthreads();
+
+  v4i af[4][KS1];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + ((16 * u + (lane & 15)) * ROWS + 4 * s + g) * 16);
+
+  const int p = P.p[i];
+  const float inv = P.inv_p[i];
+  const double invd = P.inv_pd[i];
+  for (int cg = wave; cg < ncg; cg += 4) {
+    if (cg != wave) {
+#pragma unroll
+      for (int cc = 0; cc < K1_CPW; ++cc)
+#pragma unroll
+        for (int s = 0; s < KS1; ++s)
+#pragma unroll
+          for (int pl = 0; pl < PL; ++pl) {
+            const int cbk = min(cg * K1_CPW + cc, P.CB1 - 1);
+            bf[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
+          }
+    }
+#pragma unroll
+    for (int cc = 0; cc < K1_CPW; ++cc) {
+      const int cbk = cg * K1_CPW + cc;
+      if (cbk >= P.CB1) break;
+      v4i acc[PL][4];
+#pragma unroll
+      for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[pl][u] = (v4i){0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KS1; ++s)
+#pragma unroll
+        for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            acc[pl][u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], bf[cc][s][pl], acc[pl][u], 0, 0, 0);
+      const int pt = 16 * cbk + (lane & 15);
+      int8_t *dst = V + ((((size_t)(i * P.P2 + pt) * (P.Tp >> 4) + (tau >> 4)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64 + g * 16;
+      if (WIDE) {
+        // per plane |acc| <= t*t * 128 * 128 = 2^22, so 256 * acc_h + acc_l fits 32 bits
+        v4i out_h, out_l;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          uint32_t wh = 0, wl = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int tot = acc[0][u][j] * 256 + acc[PL - 1][u][j];
+            const int v = storable16(mod_near64((long long)tot, invd, p), p);
+            const int lo = (int)(int8_t)(v & 0xFF), hi = (v - lo) >> 8;
+            wh |= ((uint32_t)hi & 0xFFu) << (8 * j);
+            wl |= ((uint32_t)lo & 0xFFu) << (8 * j);
+          }
+          out_h[u] = (int)wh;
+          out_l[u] = (int)wl;
+        }
+        if (pt < P.P2) {
+          *(v4i *)dst = out_h;
+          *(v4i *)(dst + 1024) = out_l;
+        }
+      } else {
+        // |acc| <= t*t * 126 * 128 < 2^24
+        v4i out;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          out[u] = (int)pack_low_bytes(mod_lowbyte(acc[0][u][0], inv, -p), mod_lowbyte(acc[0][u][1], inv, -p),
+                                       mod_lowbyte(acc[0][u][2], inv, -p), mod_lowbyte(acc[0][u][3], inv, -p));
+        if (pt < P.P2) *(v4i *)dst = out;
+      }
+    }
+  }
+}
+
+}  // namespace rnswino

@@ -1,0 +1,130 @@
+// K3: inverse transform on the matrix cores, fused with the conversion out of the RNS.
+//
+// Y_i = A^T_p O_i A_p after the reduction over C (paper section 6, eq. "direct_sum_2"), then the residues
+// (Y_0..Y_{n-1}) are converted to the integer result (section 3).  A^T O A = (A^T kron A^T) vec(O): per residue
+// an (m*m) x (t*t) matrix applied to the t*t transform points of a (channel k, tile) pair.  MFMA roles: A operand =
+// the Kronecker table (rows = 16 outputs), B operand = O (columns = 16 consecutive tiles of one channel k),
+// contraction index = transform point; a lane's 16 operand bytes are four O words (groups q = 16s + 4g + e).
+//
+// Conversion: the table rows are pre-multiplied by (P/p_i)^-1 mod p_i (P = prod p_i), so the reduced accumulator
+// w_i is the CRT coefficient of residue i and
+//     y = sum_i (P/p_i) w_i - P * rint(sum_i w_i / p_i)        (computed modulo 2^32)
+// is the representative of the result in [-(P-1)/2, (P-1)/2] -- the same value mixed-radix conversion with
+// symmetric digits yields; any representative of w_i gives the same y.  The rounding is done in binary64:
+// sum_i w_i/p_i = y/P + integer with |y/P| <= 1/2 - 1/(2P), and the error of the sum is below 1e-14 while
+// 1/(2P) > 1e-10 for every moduli set whose product can matter for a 32-bit result.
+//
+// Block = one (k, block of 16 tiles); its waves take the 16-output row blocks rb = wave, wave+4, ...; every wave
+// loads the O operand itself (the copies hit in L1).  No LDS.  Grid: K * Tp/16 blocks of 256 threads.
+// 16-bit moduli: table and O are two byte planes each; three accumulators as in the GEMM.
+#pragma once
+#include "kernels_common.hpp"
+
+namespace rnswino {
+
+template <int NRES, int KS3, bool WIDE>
+__global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t *__restrict__ O,
+                                                       int32_t *__restrict__ y) {
+  constexpr int PL = WIDE ? 2 : 1;
+  constexpr int NACC = WIDE ? 3 : 1;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  if (wave >= P.RB3) return;
+  const int ntb = P.Tp >> 4;
+  const int k = blockIdx.x / ntb, tb = blockIdx.x % ntb;
+  const int tau = tb * 16 + (lane & 15);
+
+  v4i of[NRES][KS3][PL];
+#pragma unroll
+  for (int i = 0; i < NRES; ++i)
+#pragma unroll
+    for (int s = 0; s < KS3; ++s)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int q = 16 * s + 4 * g + e;
+        const bool ok = q < P.Q && tau < P.T;
+        const uint32_t *src = O + ((((size_t)i * P.Q + q) * P.Kp + k) * P.Tp + tau) * PL;
+        if (WIDE) {
+          v2i two = (v2i){0, 0};
+          if (ok) two = *(const v2i *)src;
+          of[i][s][0][e] = two[0];
+          of[i][s][PL - 1][e] = two[1];
+        } else {
+          of[i][s][0][e] = ok ? (int)*src : 0;
+        }
+      }
+
+  const int m = P.m, mm = m * m;
+  const bool tile_ok = tau < P.T;
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  int32_t *yplane = y + ((size_t)img * P.K + k) * P.Ho * P.Wo;
+  const float inv_m = 1.0f / (float)m;
+  const bool vec4 = ((m & 3) == 0) && ((P.Wo & 3) == 0);   // four consecutive outputs stay in one row, 16-byte aligned
+
+  for (int rb = wave; rb < P.RB3; rb += 4) {
+    uint32_t w[NRES][4];
+#pragma unroll
+    for (int i = 0; i < NRES; ++i) {
+      v4i acc[NACC];
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) acc[a] = (v4i){0, 0, 0, 0};
+      const int8_t *ka = P.KA + (((size_t)i * P.RB3 + rb) * KS3) * (1024 * PL) + lane * 16;
+#pragma unroll
+      for (int s = 0; s < KS3; ++s) {
+        const v4i ah = *(const v4i *)(ka + (size_t)s * (1024 * PL));
+        if (WIDE) {
+          const v4i al = *(const v4i *)(ka + (size_t)s * (1024 * PL) + 1024);
+          acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, of[i][s][0], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, of[i][s][PL - 1], acc[1], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, of[i][s][0], acc[1], 0, 0, 0);
+          acc[NACC - 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, of[i][s][PL - 1], acc[NACC - 1], 0, 0, 0);
+        } else {
+          acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, of[i][s][0], acc[0], 0, 0, 0);
+        }
+      }
+      // residue shifted by +p so that it is non-negative
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (WIDE) {
+          // per accumulator |sum| <= t*t * 2^15: the combination stays below 2^40
+          const long long tot = (long long)acc[0][j] * 65536 + (long long)acc[1][j] * 256 + (long long)acc[NACC - 1][j];
+          w[i][j] = (uint32_t)(mod_near64(tot, P.inv_pd[i], P.p[i]) + P.p[i]);
+        } else {
+          // |acc| <= t*t * 126 * 127 < 2^24
+          w[i][j] = (uint32_t)(mod_near(acc[0][j], P.inv_p[i], P.p[i]) + P.p[i]);
+        }
+      }
+    }
+    int val[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t sum = 0;
+      double fs = 0.0;
+#pragma unroll
+      for (int i = 0; i < NRES; ++i) {
+        sum += P.crt24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
+        fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
+      }
+      const int kk = __double2int_rn(fs);
+      val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+    }
+    const int o0 = 16 * rb + 4 * g;
+    if (!tile_ok || o0 >= mm) continue;
+    if (vec4) {
+      const int u = (int)(((float)o0 + 0.5f) * inv_m);
+      const int v = o0 - u * m;
+      const int oy = ty * m + u, ox = tx * m + v;
+      if (oy < P.Ho && ox < P.Wo) *(v4i *)(yplane + (size_t)oy * P.Wo + ox) = (v4i){val[0], val[1], val[2], val[3]};
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int o = o0 + j;
+        const int u = (int)(((float)o + 0.5f) * inv_m);
+        const int v = o - u * m;
+        const int oy = ty * m + u, ox = tx * m + v;
+        if (o < mm && oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val[j];
+      }
+    }
+  }
+}
+
+}  // namespace rnswino

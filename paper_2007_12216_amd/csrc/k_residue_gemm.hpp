@@ -1,0 +1,127 @@
+// K2: the residue-domain GEMM  O[i][xi,nu][k][tau] = (sum_c U[i][xi,nu][k][c] V[i][xi,nu][tau][c]) mod p_i,
+// one GEMM per transform point and residue, the modulo taken after the sum over C (paper section 6, eq. "gemm").
+// int8 operands on v_mfma_i32_16x16x64_i8, int32 accumulation.
+//
+// Block = 4 waves = the 4 transform points of one group q (they end up as the 4 bytes of one O word); every
+// wave computes a 32 (k) x 16*NTB (tile) block of its point over the whole of C.  Operand fragments are read
+// straight from global memory in 1 KiB runs (layout.hpp); KS contraction steps are loaded before any is
+// consumed.  The four results of a group are exchanged through LDS so that O is written as whole words.
+//
+// 16-bit moduli: both operands are two byte planes, U = 256 Uh + Ul, V = 256 Vh + Vl, and
+//   sum U V = 65536 sum(Uh Vh) + 256 sum(Uh Vl + Ul Vh) + sum(Ul Vl):
+// four int8 MFMAs into three accumulators, combined in 64 bits and reduced once at the end.
+//
+// Grid: x = n*Q, y = ceil(Kp/32), z = ceil(Tp / (16*NTB)).
+#pragma once
+#include "kernels_common.hpp"
+
+namespace rnswino {
+
+template <int KS, int NTB, bool WIDE>
+__global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *__restrict__ U,
+                                                        const int8_t *__restrict__ V, uint32_t *__restrict__ O) {
+  constexpr int PL = WIDE ? 2 : 1;
+  constexpr int NACC = WIDE ? 3 : 1;
+  constexpr int COLS = 16 * NTB;
+  __shared__ uint32_t tile[32 * COLS * PL];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x / P.Q, q = blockIdx.x % P.Q;
+  const int pt = 4 * q + wave;
+  const int nkb = P.Kp >> 4, ntb = P.Tp >> 4, ncb = P.Cp >> 6;
+  const int kb0 = blockIdx.y * 2, tb0 = blockIdx.z * NTB;
+  const int p = P.p[i];
+  const float inv = P.inv_p[i];
+
+  v4i acc[NACC][2][NTB];
+#pragma unroll
+  for (int a = 0; a < NACC; ++a)
+#pragma unroll
+    for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) acc[a][rm][tb] = (v4i){0, 0, 0, 0};
+
+  if (pt < P.P2) {
+    const int slab = i * P.P2 + pt;
+    const int8_t *Ub = U + (size_t)slab * nkb * ncb * (1024 * PL) + lane * 16;
+    const int8_t *Vb = V + (size_t)slab * ntb * ncb * (1024 * PL) + (lane & 15) * 64 + (lane >> 4) * 16;
+    for (int s0 = 0; s0 < ncb; s0 += KS) {
+      v4i a[KS][2][PL], b[KS][NTB][PL];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+          for (int pl = 0; pl < PL; ++pl) {
+            a[s][rm][pl] = (v4i){0, 0, 0, 0};
+            if (kb0 + rm < nkb)
+              a[s][rm][pl] = *(const v4i *)(Ub + ((((size_t)(kb0 + rm) * ncb + s0 + s) * PL) + pl) * 1024);
+          }
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+          for (int pl = 0; pl < PL; ++pl) {
+            b[s][tb][pl] = (v4i){0, 0, 0, 0};
+            if (tb0 + tb < ntb)
+              b[s][tb][pl] = *(const v4i *)(Vb + ((((size_t)(tb0 + tb) * ncb + s0 + s) * PL) + pl) * 1024);
+          }
+      }
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+          for (int tb = 0; tb < NTB; ++tb) {
+            if (WIDE) {
+              acc[0][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][0], b[s][tb][0], acc[0][rm][tb], 0, 0, 0);
+              acc[1][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][0], b[s][tb][PL - 1], acc[1][rm][tb], 0, 0, 0);
+              acc[1][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][PL - 1], b[s][tb][0], acc[1][rm][tb], 0, 0, 0);
+              acc[NACC - 1][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][PL - 1], b[s][tb][PL - 1], acc[NACC - 1][rm][tb], 0, 0, 0);
+            } else {
+              acc[0][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][0], b[s][tb][0], acc[0][rm][tb], 0, 0, 0);
+            }
+          }
+      // 8-bit residues, |U|,|V| <= 127: 512 channels add at most 8.3e6, so reducing every 8 steps keeps
+      // |acc| < 2^24.  (Byte planes need nothing here: a step adds at most 2^21 and C is below 2^14.)
+      if (!WIDE && (((s0 + KS) & 7) == 0) && (s0 + KS < ncb)) {
+#pragma unroll
+        for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+          for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[0][rm][tb][j] = mod_near(acc[0][rm][tb][j], inv, p);
+      }
+    }
+  }
+
+  uint8_t *tile8 = (uint8_t *)tile;
+#pragma unroll
+  for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = rm * 16 + 4 * (lane >> 4) + j, col = tb * 16 + (lane & 15);
+        if (WIDE) {
+          const long long tot = (long long)acc[0][rm][tb][j] * 65536 + (long long)acc[1][rm][tb][j] * 256 +
+                                (long long)acc[NACC - 1][rm][tb][j];
+          const int v = storable16(mod_near64(tot, P.inv_pd[i], p), p);
+          const int lo = (int)(int8_t)(v & 0xFF), hi = (v - lo) >> 8;
+          tile8[((row * COLS + col) * PL) * 4 + wave] = (uint8_t)hi;
+          tile8[((row * COLS + col) * PL + PL - 1) * 4 + wave] = (uint8_t)lo;
+        } else {
+          tile8[(row * COLS + col) * 4 + wave] = (uint8_t)mod_lowbyte(acc[0][rm][tb][j], inv, -p);
+        }
+      }
+  __syncthreads();
+  uint32_t *Ob = O + ((size_t)i * P.Q + q) * P.Kp * P.Tp * PL;
+  constexpr int ROWW = COLS * PL;   // words per tile row
+#pragma unroll
+  for (int it = 0; it < (32 * ROWW) / 256; ++it) {
+    const int e = it * 256 + threadIdx.x;
+    const int row = e / ROWW, rem = e % ROWW;
+    const int k = kb0 * 16 + row, tau = tb0 * 16 + rem / PL;
+    if (k < P.Kp && tau < P.T) Ob[((size_t)k * P.Tp + tb0 * 16) * PL + rem] = tile[e];   // padding tiles are neither written nor read
+  }
+}
+
+}  // namespace rnswino

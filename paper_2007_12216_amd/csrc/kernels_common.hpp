@@ -1,0 +1,77 @@
+// Shared device-side definitions of the rnswino kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "layout.hpp"
+
+namespace rnswino {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+// Everything a kernel needs to know about the layer, passed by value.
+struct KParams {
+  int N, C, K, H, W, r, m, t, pad;
+  int Ho, Wo, th, tw, T, n;
+  int Cp, Kp, Tp, P2, Q;
+  int p[8];
+  float inv_p[8];
+  double inv_pd[8];           // 1 / p_i
+  const int32_t *G;           // device table [n][t*r] for the filter transform
+  // transforms on the matrix cores: Kronecker tables in operand-fragment order (see plan_math.cpp)
+  int CB1, KS1, RB3, KS3;
+  const int8_t *KB;           // (B^T kron B^T) mod p          [n][CB1][KS1][planes][64 lanes][16]
+  const int8_t *KA;           // (A^T kron A^T) crt_inv mod p  [n][RB3][KS3][planes][64 lanes][16]
+  uint32_t crt_c[8];          // prod_{l != i} p_l mod 2^32
+  uint32_t prod_mod32;        // prod p_i mod 2^32
+  int crt24;                  // every prod_{l != i} p_l is below 2^24: 24-bit multiplies suffice
+};
+
+// ---- residues of 8-bit moduli -------------------------------------------------------------------
+
+// Residue of x modulo p for |x| < 2^24 and p <= 253, without division: q = rint(x/p) from one fused
+// multiply-add against 1.5*2^23 (whose mantissa then holds q), r = x - q p.  1/p carries a relative error
+// of 2^-24, so |x/p - q| <= 1/2 + |x| 2^-24 / p and |r| <= p/2 + 1: a valid representative that fits int8
+// (|r| <= 127), not always the canonical one.
+__device__ __forceinline__ int mod_near(int x, float inv_p, int p) {
+  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
+  const int q = __float_as_int(f) - 0x4B400000;
+  return x - __mul24(q, p);
+}
+
+// Low byte of that residue: the constant term 2^22 * p of the mantissa trick is a multiple of 256 and drops out.
+__device__ __forceinline__ uint32_t mod_lowbyte(int x, float inv_p, int neg_p) {
+  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
+  return (uint32_t)(__mul24(__float_as_int(f), neg_p) + x);
+}
+
+// byte 0 of a, b, c, d -> one word
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);
+  const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+  return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
+}
+
+// ---- residues of 16-bit moduli ------------------------------------------------------------------
+// A residue is stored as two signed bytes, value = 256*h + l, which covers [-32896, 32639]; every class
+// modulo p <= 65521 has a representative there.
+
+// representative of x modulo p with |r| <= p/2 + 1, |x| < 2^52 (binary64 quotient estimate)
+__device__ __forceinline__ int mod_near64(long long x, double inv_pd, int p) {
+  const long long q = __double2ll_rn((double)x * inv_pd);
+  return (int)(x - q * (long long)p);
+}
+
+// move a representative with |r| <= 32761 into the storable range
+__device__ __forceinline__ int storable16(int r, int p) { return r > 32639 ? r - p : r; }
+
+__device__ __forceinline__ int sym_mod64(long long v, int p) {   // exact, slow; offline kernels only
+  int r = (int)(v % p);
+  const int h = (p - 1) >> 1;
+  if (r > h) r -= p;
+  if (r < -h) r += p;
+  return r;
+}
+
+}  // namespace rnswino

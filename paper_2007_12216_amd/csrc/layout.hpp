@@ -19,8 +19,9 @@
 //
 // n moduli, t*t transform points, Cp = C rounded up to 64 (padding channels are
 // zero in U), Kp = K rounded up to 16, Tp = T rounded up to 16, Q = ceil(t*t/4).
-// For 16-bit moduli every element is two bytes wide and the same element offsets
-// are used.
+// For 16-bit moduli a residue is two signed bytes (value = 256*h + l) kept in two
+// planes, h first: every U and V fragment becomes 2 KiB ([plane][...]), and every
+// O word becomes a pair of words ([..][Tp][plane][4 B]).
 #pragma once
 #include <cstddef>
 #include <cstdint>
@@ -54,6 +55,23 @@ RNSW_HD size_t v_offset(int slab, int tau, int c, int Tp, int Cp) {
 
 RNSW_HD size_t o_offset(int i, int pt, int k, int tau, int Q, int Kp, int Tp) {
   return ((((size_t)i * Q + (pt >> 2)) * Kp + k) * Tp + tau) * 4 + (pt & 3);
+}
+
+RNSW_HD size_t u_offset_wide(int slab, int k, int c, int Kp, int Cp, int plane) {
+  const int kb = k >> 4, cb = c >> 6;
+  const int pos = chan_pos64(c & 63);
+  const int g = pos >> 4, b = pos & 15;
+  const size_t frag = (size_t)slab * (Kp >> 4) * (Cp >> 6) + (size_t)kb * (Cp >> 6) + cb;
+  return frag * 2048 + (size_t)plane * 1024 + (size_t)(((k & 15) + 16 * g) * 16 + b);
+}
+
+RNSW_HD size_t v_offset_wide(int slab, int tau, int c, int Tp, int Cp, int plane) {
+  const size_t frag = ((size_t)slab * (Tp >> 4) + (tau >> 4)) * (Cp >> 6) + (c >> 6);
+  return frag * 2048 + (size_t)plane * 1024 + (size_t)((tau & 15) * 64 + chan_pos64(c & 63));
+}
+
+RNSW_HD size_t o_offset_wide(int i, int pt, int k, int tau, int Q, int Kp, int Tp, int plane) {
+  return (((((size_t)i * Q + (pt >> 2)) * Kp + k) * Tp + tau) * 2 + plane) * 4 + (pt & 3);
 }
 
 }  // namespace rnswino

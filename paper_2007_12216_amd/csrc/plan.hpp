@@ -35,6 +35,13 @@ int validate_desc(const rnswino_desc_t &d, Dims &dims);            // fills dims
 
 }  // namespace rnswino
 
+struct rnswino_plan_s;
+namespace rnswino {
+// Fills the CRT constants of the plan and lays out every table the kernels read into one host blob
+// (offsets are stored in the plan).  Host only.
+void build_tables(rnswino_plan_s &plan, std::vector<char> &blob);
+}
+
 struct rnswino_plan_s {
   rnswino_desc_t desc;
   rnswino::Dims dims;
@@ -49,6 +56,6 @@ struct rnswino_plan_s {
   void *d_tables;                           // one device allocation holding every table below
   size_t d_tables_bytes;
   // offsets (bytes) into d_tables
-  size_t off_AT, off_G, off_BT;             // int32 matrices, [n][...]
-  size_t off_KB, off_KA;                    // int8 Kronecker tables for the MFMA transforms (see kernels)
+  size_t off_G;                             // int32 G matrices [n][t*r] (filter transform)
+  size_t off_KB, off_KA;                    // int8 Kronecker tables of the input / inverse transform
 };

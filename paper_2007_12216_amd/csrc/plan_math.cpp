@@ -17,6 +17,7 @@
 #include "plan.hpp"
 
 #include <cstdlib>
+#include <cstring>
 #include <numeric>
 
 namespace rnswino {
@@ -172,6 +173,99 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   o.RB3 = (d.m * d.m + 15) / 16;
   o.KS3 = (o.P2 + 63) / 64;
   return RNSWINO_OK;
+}
+
+
+// ---------------------------------------------------------------------------------------------------
+// Tables read by the kernels.
+//
+// The 2-D transforms are applied as Kronecker products on the matrix cores:
+//   vec(B^T d B) = (B^T kron B^T) vec(d),      vec(A^T O A) = (A^T kron A^T) vec(O),
+// so each residue needs a (t*t) x (t*t) and an (m*m) x (t*t) matrix modulo p.  They are stored in the operand
+// fragment order of v_mfma_i32_16x16x64_i8: a fragment is 16 rows (or columns) x 64 contraction elements,
+// lane l holds row l%16 and the 16 contraction elements of slice g = l/16.
+//   KB (input transform, B operand): fragment (cbk, s): column = transform point 16*cbk + l%16,
+//       contraction element (g, b) = pixel (row 4s+g, column b) of the tile; zero for b >= t or row >= t.
+//   KA (inverse transform, A operand): fragment (rb, s): row = output u*m+v = 16*rb + l%16,
+//       contraction element (g, b) = transform point 64s + 16g + b.  Each entry is multiplied by
+//       (P/p_i)^-1 mod p_i so that the kernel's accumulator is directly the CRT coefficient of the residue.
+// 8-bit moduli: one signed byte per entry (symmetric residue).  16-bit moduli: two byte planes h, l with
+// entry = 256 h + l, the representative chosen in [-32896, 32639].
+// ---------------------------------------------------------------------------------------------------
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static void put_entry(int8_t *frag, int planes, int lane, int b, int32_t sym, int64_t p) {
+  if (planes == 1) {
+    frag[lane * 16 + b] = (int8_t)sym;
+  } else {
+    int32_t v = sym > 32639 ? sym - (int32_t)p : sym;
+    const int32_t lo = (int32_t)(int8_t)(v & 0xFF), hi = (v - lo) >> 8;
+    frag[lane * 16 + b] = (int8_t)hi;
+    frag[1024 + lane * 16 + b] = (int8_t)lo;
+  }
+}
+
+void build_tables(rnswino_plan_s &pl, std::vector<char> &blob) {
+  const Dims &d = pl.dims;
+  const rnswino_desc_t &desc = pl.desc;
+  // CRT constants: c_i = prod_{l != i} p_l (mod 2^32), its inverse modulo p_i, and P mod 2^32
+  pl.prod_mod32 = 1;
+  for (int i = 0; i < d.n; ++i) {
+    uint32_t c32 = 1;
+    int64_t cmod = 1;
+    unsigned __int128 full = 1;
+    for (int l = 0; l < d.n; ++l)
+      if (l != i) {
+        c32 *= desc.moduli[l];
+        cmod = (cmod * (int64_t)desc.moduli[l]) % (int64_t)desc.moduli[i];
+        full *= desc.moduli[l];
+        if (full > ((unsigned __int128)1 << 40)) full = (unsigned __int128)1 << 40;
+      }
+    pl.crt_c[i] = c32;
+    pl.crt_c_exact_small[i] = full < ((unsigned __int128)1 << 24) ? 1 : 0;
+    pl.crt_inv[i] = (uint32_t)mod_inverse(cmod, desc.moduli[i]);
+    pl.prod_mod32 *= desc.moduli[i];
+  }
+
+  const int planes = d.wide ? 2 : 1;
+  const size_t szG = (size_t)d.n * d.t * d.r * 4;
+  const size_t szKB = (size_t)d.n * d.CB1 * d.KS1 * planes * 1024;
+  const size_t szKA = (size_t)d.n * d.RB3 * d.KS3 * planes * 1024;
+  pl.off_G = 0;
+  pl.off_KB = align256(pl.off_G + szG);
+  pl.off_KA = align256(pl.off_KB + szKB);
+  pl.d_tables_bytes = align256(pl.off_KA + szKA);
+  blob.assign(pl.d_tables_bytes, 0);
+
+  for (int i = 0; i < d.n; ++i) {
+    const int64_t p = desc.moduli[i];
+    const std::vector<int32_t> &BT = pl.tf[i].BT, &AT = pl.tf[i].AT;
+    std::memcpy(blob.data() + pl.off_G + (size_t)i * d.t * d.r * 4, pl.tf[i].G.data(), (size_t)d.t * d.r * 4);
+    int8_t *kb = (int8_t *)blob.data() + pl.off_KB + (size_t)i * d.CB1 * d.KS1 * planes * 1024;
+    for (int cbk = 0; cbk < d.CB1; ++cbk)
+      for (int s = 0; s < d.KS1; ++s)
+        for (int lane = 0; lane < 64; ++lane)
+          for (int b = 0; b < 16; ++b) {
+            const int pt = 16 * cbk + (lane & 15), a = 4 * s + (lane >> 4);
+            int32_t v = 0;
+            if (pt < d.P2 && a < d.t && b < d.t)
+              v = sym_residue((int64_t)BT[(size_t)(pt / d.t) * d.t + a] * BT[(size_t)(pt % d.t) * d.t + b], p);
+            put_entry(kb + (size_t)(cbk * d.KS1 + s) * planes * 1024, planes, lane, b, v, p);
+          }
+    int8_t *ka = (int8_t *)blob.data() + pl.off_KA + (size_t)i * d.RB3 * d.KS3 * planes * 1024;
+    for (int rb = 0; rb < d.RB3; ++rb)
+      for (int s = 0; s < d.KS3; ++s)
+        for (int lane = 0; lane < 64; ++lane)
+          for (int b = 0; b < 16; ++b) {
+            const int o = 16 * rb + (lane & 15), pt = 64 * s + 16 * (lane >> 4) + b;
+            int32_t v = 0;
+            if (o < d.m * d.m && pt < d.P2) {
+              const int64_t aa = (int64_t)AT[(size_t)(o / d.m) * d.t + pt / d.t] * AT[(size_t)(o % d.m) * d.t + pt % d.t];
+              v = sym_residue(sym_residue(aa, p) * (int64_t)pl.crt_inv[i], p);
+            }
+            put_entry(ka + (size_t)(rb * d.KS3 + s) * planes * 1024, planes, lane, b, v, p);
+          }
+  }
 }
 
 }  // namespace rnswino
