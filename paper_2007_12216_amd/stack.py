@@ -1,0 +1,59 @@
+"""A chain of stride-1 int8 convolution layers with shift/clamp re-quantisation and optional 2x2 max-pool
+between them (the 13-layer VGG16-style workload).  Plumbing only: every step is a C-ABI call."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class ConvStack:
+    def __init__(self, layers, device="cuda:0"):
+        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool (see synth_inputs.vgg16_stack)."""
+        if not torch.cuda.is_available():
+            raise RuntimeError("rnswino needs a GPU: there is no CPU execution path")
+        self.device = torch.device(device)
+        self.cfg = [dict(l) for l in layers]
+        self.plans, self.U, self.act = [], [], []
+        ws_bytes, y_elems = 0, 0
+        with torch.cuda.device(self.device):
+            for l in self.cfg:
+                p = B.rnswino_plan(l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["m"], l["pad"], l["moduli"])
+                self.plans.append(p)
+                self.U.append(torch.empty(B.rnswino_filter_bytes(p), dtype=torch.uint8, device=self.device))
+                ws_bytes = max(ws_bytes, B.rnswino_workspace_bytes(p))
+                y_elems = max(y_elems, l["N"] * l["K"] * p.Ho * p.Wo)
+                Hq, Wq = (p.Ho // 2, p.Wo // 2) if l["pool"] else (p.Ho, p.Wo)
+                self.act.append(torch.empty((l["N"], l["K"], Hq, Wq), dtype=torch.int8, device=self.device))
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device)
+        self.y = torch.empty(y_elems, dtype=torch.int32, device=self.device)
+
+    def _stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def set_weights(self, weights) -> None:
+        """weights: one int8 [K][C][r][r] array per layer; runs the offline filter transforms."""
+        self.w = []
+        for p, U, w in zip(self.plans, self.U, weights):
+            wd = torch.from_numpy(np.ascontiguousarray(w)).to(self.device)
+            self.w.append(wd)
+            B.rnswino_filter_transform(p, wd, U, self._stream())
+
+    def forward(self, x: torch.Tensor, keep_last_y: bool = False):
+        """x: int8 [N][C][H][W] of the first layer.  Returns the int8 activations of the last layer
+        (and its raw int32 output if asked)."""
+        st = self._stream()
+        a = x
+        for l, p, U, out in zip(self.cfg, self.plans, self.U, self.act):
+            B.rnswino_conv2d(p, a, U, self.y, self.workspace, st)
+            B.rnswino_requant_pool(self.y, out, l["N"] * l["K"], p.Ho, p.Wo, l["shift"], l["pool"], st)
+            a = out
+        if keep_last_y:
+            p = self.plans[-1]
+            n = self.cfg[-1]["N"] * self.cfg[-1]["K"] * p.Ho * p.Wo
+            return a, self.y[:n].view(self.cfg[-1]["N"], self.cfg[-1]["K"], p.Ho, p.Wo)
+        return a
+
+    def direct_ops(self) -> float:
+        return float(sum(2.0 * l["N"] * l["K"] * l["C"] * p.Ho * p.Wo * l["r"] ** 2 for l, p in zip(self.cfg, self.plans)))

@@ -134,3 +134,54 @@ def test_requant_pool_matches_the_oracle_glue():
         if pool:
             ref = maxpool2x2(ref)
         assert np.array_equal(a.cpu().numpy(), ref)
+
+
+def oracle_stack(layers, x, weights):
+    """The 13-layer chain on the CPU: direct convolution, shift/clamp, optional 2x2 max-pool; all activations."""
+    from oracle import requant_shift_clamp, maxpool2x2
+    acts, a, y = [], x, None
+    for l, w in zip(layers, weights):
+        y = direct_conv2d(a, w, l["pad"])
+        a = requant_shift_clamp(y, l["shift"])
+        if l["pool"]:
+            a = maxpool2x2(a)
+        acts.append(a)
+    return acts, y
+
+
+@pytest.mark.parametrize("batch,hw", [(2, 32), (1, 48)])
+def test_vgg16_stack_reduced_plane(batch, hw):
+    from paper_2007_12216_amd.stack import ConvStack
+    print("stack", batch, hw, flush=True)
+    layers = si.vgg16_stack(batch=batch, hw=hw)
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
+    stack = ConvStack(layers)
+    stack.set_weights(weights)
+    a, y = stack.forward(torch.from_numpy(x).to("cuda:0"), keep_last_y=True)
+    torch.cuda.synchronize()
+    ref_acts, ref_y = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+    assert np.array_equal(y.cpu().numpy(), ref_y)
+    # the re-quantisation keeps the activations alive: neither all zero nor all saturated
+    last = ref_acts[-1].astype(np.int32)
+    assert (last != 0).mean() > 0.5 and (np.abs(last) >= 127).mean() < 0.5
+
+
+def test_vgg16_stack_full_size():
+    """Workload 5: batch 8, 224x224, all 13 layers; every layer's activations bit-exact against the CPU chain."""
+    from paper_2007_12216_amd.stack import ConvStack
+    print("stack full size", flush=True)
+    layers = si.vgg16_stack(batch=8, hw=224)
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    x = si.int8_tensor(si.VGG16_SEED_X, (8, 3, 224, 224))
+    stack = ConvStack(layers)
+    stack.set_weights(weights)
+    a, y = stack.forward(torch.from_numpy(x).to("cuda:0"), keep_last_y=True)
+    torch.cuda.synchronize()
+    print("gpu done; oracle chain ...", flush=True)
+    ref_acts, ref_y = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+    assert np.array_equal(y.cpu().numpy(), ref_y)
