@@ -13,7 +13,8 @@ layer after layer would.  The same loop on one buffer set ("warm") is reported b
 
 One JSON line is printed: the contract fields plus
   roofline     -- the slowest of the three kernels: algorithmic bytes per launch / its average duration, measured
-                  with HIP events recorded around each kernel on the launch stream, against 8 TB/s HBM;
+                  with HIP events that take each kernel's own start and stop timestamps on the launch stream
+                  (a second pass over the same rotation, same step count), against 8 TB/s HBM;
   cpu_baseline -- the direct-convolution oracle timed on this machine's host cores (context only).
 """
 from __future__ import annotations
@@ -147,7 +148,7 @@ def main():
 
     # ---- per-kernel durations: HIP events around each kernel, same cold rotation, same step count ----------
     evs = HipEvents()
-    ev = [[evs.create() for _ in range(4)] for _ in range(K_steps)]
+    ev = [[evs.create() for _ in range(6)] for _ in range(K_steps)]
     for k in range(W_steps):
         step_cold(k)
     torch.cuda.synchronize()
@@ -159,7 +160,7 @@ def main():
     stage_ms = {nm: 0.0 for nm in names}
     for k in range(K_steps):
         for j, nm in enumerate(names):
-            stage_ms[nm] += evs.elapsed_ms(ev[k][j], ev[k][j + 1])
+            stage_ms[nm] += evs.elapsed_ms(ev[k][2 * j], ev[k][2 * j + 1])
     for nm in names:
         stage_ms[nm] /= K_steps
     evs.destroy_all()

@@ -109,7 +109,8 @@ int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, vo
  * transform point and residue with the modulo after the sum, inverse transform A^T (.) A after that
  * reduction, mixed-radix conversion to int32.
  * x_dev: int8 [N][C][H][W].  U_dev: from rnswino_filter_transform.  y_dev: int32 [N][K][Ho][Wo].
- * workspace_dev: rnswino_workspace_bytes() bytes, 256-byte aligned; contents are scratch.
+ * workspace_dev: rnswino_workspace_bytes() bytes, 256-byte aligned; contents are scratch.  U_dev, workspace_dev
+ * and y_dev must be 16-byte aligned (E_INVALID otherwise); x_dev may have any alignment.
  * When the plan passed the range test, y equals the direct convolution
  *   y[n][k][oy][ox] = sum_{c,i,j} xpad[n][c][oy+i-pad][ox+j-pad] * w[k][c][i][j]
  * (correlation orientation of section 3.1) bit for bit.
@@ -118,13 +119,13 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
                    int32_t *y_dev, void *workspace_dev, void *stream);
 
 /*
- * rnswino_conv2d with four caller-created hipEvent_t (passed as void*) recorded on `stream`: events[0] before
- * the input transform, events[1] between input transform and residue GEMM, events[2] between GEMM and inverse
- * transform, events[3] after the inverse transform + mixed-radix conversion.  For per-stage measurement
+ * rnswino_conv2d with six caller-created hipEvent_t (passed as void*): events[2j] and events[2j+1] receive the
+ * start and stop timestamps of kernel j (0: input transform, 1: residue GEMM, 2: inverse transform + conversion),
+ * so hipEventElapsedTime(events[2j], events[2j+1]) is that kernel's own duration.  For per-stage measurement
  * (the paper's time breakdown of section 8); does not synchronise.
  */
 int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
-                          void *workspace_dev, void *stream, void *const events[4]);
+                          void *workspace_dev, void *stream, void *const events[6]);
 
 /*
  * Glue for chaining layers (not part of the paper's method; the 13-layer stack workload needs it):

@@ -163,8 +163,8 @@ def rnswino_conv2d(plan: Plan, x_dev, U_dev, y_dev, workspace_dev, stream: int =
 
 
 def rnswino_conv2d_events(plan: Plan, x_dev, U_dev, y_dev, workspace_dev, stream: int, events) -> None:
-    """events: sequence of four hipEvent_t handles (ints)."""
-    arr = (ctypes.c_void_p * 4)(*[int(e) for e in events])
+    """events: six hipEvent_t handles (ints): (start, stop) of the three kernels."""
+    arr = (ctypes.c_void_p * 6)(*[int(e) for e in events])
     _check(lib().rnswino_conv2d_events(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev), _ptr(workspace_dev), stream, arr),
            "rnswino_conv2d_events")
 

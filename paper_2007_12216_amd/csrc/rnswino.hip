@@ -6,6 +6,7 @@
 //   K2  residue GEMM       O = sum_c U V mod p               (int8 MFMA)                      k_residue_gemm.hpp
 //   K3  inverse transform  Y = A^T O A mod p, then CRT to int32 (int8 MFMA, Kronecker form)   k_inverse_crt.hpp
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstring>
@@ -59,15 +60,28 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? RNSWINO_OK
 
 inline unsigned blocks_for(long long total, int bs) { return (unsigned)((total + bs - 1) / bs); }
 
+// Optional pair of events that receive the kernel's own start and stop timestamps.
+struct Timing {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+
+template <typename Kern, typename... Args>
+inline void launch(Kern kern, dim3 grid, hipStream_t st, Timing tm, Args... args) {
+  if (tm.start || tm.stop)
+    hipExtLaunchKernelGGL(kern, grid, dim3(256), 0, st, tm.start, tm.stop, 0, args...);
+  else
+    hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, args...);
+}
+
 // ---- K1 ----
 template <bool WIDE>
-void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st) {
+void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
   const dim3 grid((unsigned)(d.T * (d.Cp / 64)), (unsigned)d.n);
   switch (d.KS1) {
-    case 1: hipLaunchKernelGGL((k1_input_transform<1, WIDE>), grid, dim3(256), 0, st, P, x, V); break;
-    case 2: hipLaunchKernelGGL((k1_input_transform<2, WIDE>), grid, dim3(256), 0, st, P, x, V); break;
-    case 3: hipLaunchKernelGGL((k1_input_transform<3, WIDE>), grid, dim3(256), 0, st, P, x, V); break;
-    default: hipLaunchKernelGGL((k1_input_transform<4, WIDE>), grid, dim3(256), 0, st, P, x, V); break;
+    case 1: launch(k1_input_transform<1, WIDE>, grid, st, tm, P, x, V); break;
+    case 2: launch(k1_input_transform<2, WIDE>, grid, st, tm, P, x, V); break;
+    case 3: launch(k1_input_transform<3, WIDE>, grid, st, tm, P, x, V); break;
+    default: launch(k1_input_transform<4, WIDE>, grid, st, tm, P, x, V); break;
   }
 }
 
@@ -75,51 +89,51 @@ void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipS
 // NTB = 16-tile column blocks per wave (1, 2 or 4, the smallest that covers Tp up to 64); KS = contraction steps
 // in flight, limited by the register budget of the variant.
 template <int KS, int NTB, bool WIDE>
-void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st) {
+void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
   const dim3 grid((unsigned)(d.n * d.Q), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp / 16 + NTB - 1) / NTB));
-  hipLaunchKernelGGL((k2_residue_gemm<KS, NTB, WIDE>), grid, dim3(256), 0, st, P, U, V, O);
+  launch(k2_residue_gemm<KS, NTB, WIDE>, grid, st, tm, P, U, V, O);
 }
 
 template <int NTB, bool WIDE>
-void launch_k2_ntb(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st) {
+void launch_k2_ntb(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
   const int ncb = d.Cp / 64;
   constexpr int KSMAX = WIDE ? (NTB == 1 ? 4 : NTB == 2 ? 2 : 1) : 4;
-  if (KSMAX >= 4 && ncb % 4 == 0) launch_k2_one<4, NTB, WIDE>(d, P, U, V, O, st);
-  else if (KSMAX >= 2 && ncb % 2 == 0) launch_k2_one<2, NTB, WIDE>(d, P, U, V, O, st);
-  else launch_k2_one<1, NTB, WIDE>(d, P, U, V, O, st);
+  if (KSMAX >= 4 && ncb % 4 == 0) launch_k2_one<4, NTB, WIDE>(d, P, U, V, O, st, tm);
+  else if (KSMAX >= 2 && ncb % 2 == 0) launch_k2_one<2, NTB, WIDE>(d, P, U, V, O, st, tm);
+  else launch_k2_one<1, NTB, WIDE>(d, P, U, V, O, st, tm);
 }
 
 template <bool WIDE>
-void launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st) {
+void launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
   const int ntb = d.Tp / 16;
-  if (ntb == 1) launch_k2_ntb<1, WIDE>(d, P, U, V, O, st);
-  else if (ntb == 2) launch_k2_ntb<2, WIDE>(d, P, U, V, O, st);
-  else launch_k2_ntb<4, WIDE>(d, P, U, V, O, st);
+  if (ntb == 1) launch_k2_ntb<1, WIDE>(d, P, U, V, O, st, tm);
+  else if (ntb == 2) launch_k2_ntb<2, WIDE>(d, P, U, V, O, st, tm);
+  else launch_k2_ntb<4, WIDE>(d, P, U, V, O, st, tm);
 }
 
 // ---- K3 ----
 template <int NRES, bool WIDE>
-void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st) {
+void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
   const dim3 grid((unsigned)(d.K * (d.Tp / 16)));
   switch (d.KS3) {
-    case 1: hipLaunchKernelGGL((k3_inverse_crt<NRES, 1, WIDE>), grid, dim3(256), 0, st, P, O, y); break;
-    case 2: hipLaunchKernelGGL((k3_inverse_crt<NRES, 2, WIDE>), grid, dim3(256), 0, st, P, O, y); break;
-    case 3: hipLaunchKernelGGL((k3_inverse_crt<NRES, 3, WIDE>), grid, dim3(256), 0, st, P, O, y); break;
-    default: hipLaunchKernelGGL((k3_inverse_crt<NRES, 4, WIDE>), grid, dim3(256), 0, st, P, O, y); break;
+    case 1: launch(k3_inverse_crt<NRES, 1, WIDE>, grid, st, tm, P, O, y); break;
+    case 2: launch(k3_inverse_crt<NRES, 2, WIDE>, grid, st, tm, P, O, y); break;
+    case 3: launch(k3_inverse_crt<NRES, 3, WIDE>, grid, st, tm, P, O, y); break;
+    default: launch(k3_inverse_crt<NRES, 4, WIDE>, grid, st, tm, P, O, y); break;
   }
 }
 
 template <bool WIDE>
-void launch_k3(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st) {
+void launch_k3(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
   switch (d.n) {
-    case 1: launch_k3_nres<1, WIDE>(d, P, O, y, st); break;
-    case 2: launch_k3_nres<2, WIDE>(d, P, O, y, st); break;
-    case 3: launch_k3_nres<3, WIDE>(d, P, O, y, st); break;
-    case 4: launch_k3_nres<4, WIDE>(d, P, O, y, st); break;
-    case 5: launch_k3_nres<5, WIDE>(d, P, O, y, st); break;
-    case 6: launch_k3_nres<6, WIDE>(d, P, O, y, st); break;
-    case 7: launch_k3_nres<7, WIDE>(d, P, O, y, st); break;
-    default: launch_k3_nres<8, WIDE>(d, P, O, y, st); break;
+    case 1: launch_k3_nres<1, WIDE>(d, P, O, y, st, tm); break;
+    case 2: launch_k3_nres<2, WIDE>(d, P, O, y, st, tm); break;
+    case 3: launch_k3_nres<3, WIDE>(d, P, O, y, st, tm); break;
+    case 4: launch_k3_nres<4, WIDE>(d, P, O, y, st, tm); break;
+    case 5: launch_k3_nres<5, WIDE>(d, P, O, y, st, tm); break;
+    case 6: launch_k3_nres<6, WIDE>(d, P, O, y, st, tm); break;
+    case 7: launch_k3_nres<7, WIDE>(d, P, O, y, st, tm); break;
+    default: launch_k3_nres<8, WIDE>(d, P, O, y, st, tm); break;
   }
 }
 
@@ -133,16 +147,15 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
   hipStream_t st = (hipStream_t)stream;
   int8_t *Vp = (int8_t *)workspace_dev;
   uint32_t *Op = (uint32_t *)((char *)workspace_dev + align256(v_bytes(d)));
-  auto mark = [&](int e) {
-    if (events && events[e]) (void)hipEventRecord((hipEvent_t)events[e], st);
-  };
-  mark(0);
-  if (d.wide) launch_k1<true>(d, P, x_dev, Vp, st); else launch_k1<false>(d, P, x_dev, Vp, st);
-  mark(1);
-  if (d.wide) launch_k2<true>(d, P, (const int8_t *)U_dev, Vp, Op, st); else launch_k2<false>(d, P, (const int8_t *)U_dev, Vp, Op, st);
-  mark(2);
-  if (d.wide) launch_k3<true>(d, P, Op, y_dev, st); else launch_k3<false>(d, P, Op, y_dev, st);
-  mark(3);
+  Timing t1, t2, t3;
+  if (events) {
+    t1.start = (hipEvent_t)events[0]; t1.stop = (hipEvent_t)events[1];
+    t2.start = (hipEvent_t)events[2]; t2.stop = (hipEvent_t)events[3];
+    t3.start = (hipEvent_t)events[4]; t3.stop = (hipEvent_t)events[5];
+  }
+  if (d.wide) launch_k1<true>(d, P, x_dev, Vp, st, t1); else launch_k1<false>(d, P, x_dev, Vp, st, t1);
+  if (d.wide) launch_k2<true>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2); else launch_k2<false>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2);
+  if (d.wide) launch_k3<true>(d, P, Op, y_dev, st, t3); else launch_k3<false>(d, P, Op, y_dev, st, t3);
   return launch_status();
 }
 
@@ -238,7 +251,7 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
 }
 
 int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
-                          void *workspace_dev, void *stream, void *const events[4]) {
+                          void *workspace_dev, void *stream, void *const events[6]) {
   if (!events) return RNSWINO_E_INVALID;
   return conv2d_impl(plan, x_dev, U_dev, y_dev, workspace_dev, stream, events);
 }
