@@ -14,7 +14,8 @@
 // every fourth group of K1_CPW column blocks.  Accumulator rows are channels 4g+j, so the four channel groups u
 // give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
 // 16-bit moduli: the table has a high and a low byte plane, V = (256 * sum_h + sum_l) mod p, stored as two planes.
-// Grid: x = T * Cp/64, y = n; 256 threads; 64 * 4*KS1 * 16 bytes of LDS.
+// Grid: x = T * Cp/64 rounded up to a multiple of 8 (see xcd_chunked), y = n (one residue per block) or 1 (the block
+// walks over all residues with the same gathered patch); 256 threads; 64 * 4*KS1 * 16 bytes of LDS.
 #pragma once
 #include "kernels_common.hpp"
 
@@ -30,8 +31,10 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   __shared__ __attribute__((aligned(16))) uint8_t xs[64 * ROWS * 16];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
   const int ncb = P.Cp >> 6;
-  const int i = blockIdx.y;
-  const int cb = blockIdx.x % ncb, tau = blockIdx.x / ncb;
+  const int i0 = gridDim.y == 1 ? 0 : blockIdx.y, i1 = gridDim.y == 1 ? P.n : i0 + 1;   // residues of this block
+  const int unit = xcd_chunked(blockIdx.x, gridDim.x, P.T * ncb);   // neighbouring tiles (shared image lines) on one XCD
+  if (unit < 0) return;
+  const int cb = unit % ncb, tau = unit / ncb;
   const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
   const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
   {
@@ -71,7 +74,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   // table fragments of this wave's first column-block group: issued before the barrier so that their latency
   // overlaps the gather
   const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
-  const int8_t *KBi = P.KB + (size_t)i * P.CB1 * KS1 * PL * 1024 + lane * 16;
+  const int8_t *KBi = P.KB + (size_t)i0 * P.CB1 * KS1 * PL * 1024 + lane * 16;
   v4i bf[K1_CPW][KS1][PL];
 #pragma unroll
   for (int cc = 0; cc < K1_CPW; ++cc)
@@ -90,11 +93,13 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
 #pragma unroll
     for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + ((16 * u + (lane & 15)) * ROWS + 4 * s + g) * 16);
 
+  for (int i = i0; i < i1; ++i) {
+  KBi = P.KB + (size_t)i * P.CB1 * KS1 * PL * 1024 + lane * 16;
   const int p = P.p[i];
   const float inv = P.inv_p[i];
   const double invd = P.inv_pd[i];
   for (int cg = wave; cg < ncg; cg += 4) {
-    if (cg != wave) {
+    if (cg != wave || i != i0) {
 #pragma unroll
       for (int cc = 0; cc < K1_CPW; ++cc)
 #pragma unroll
@@ -155,6 +160,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
       }
     }
   }
+  }  // residues
 }
 
 }  // namespace rnswino

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
       for (int e = 0; e < 4; ++e) {
         const int q = 16 * s + 4 * g + e;
         const bool ok = q < P.Q && tau < P.T;
-        const uint32_t *src = O + ((((size_t)i * P.Q + q) * P.Kp + k) * P.Tp + tau) * PL;
+        const uint32_t *src = O + ((((size_t)k * P.n + i) * P.Q + q) * P.Tp + tau) * PL;
         if (WIDE) {
           v2i two = (v2i){0, 0};
           if (ok) two = *(const v2i *)src;
@@ -126,5 +126,6 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
     }
   }
 }
+
 
 }  // namespace rnswino

@@ -11,7 +11,8 @@
 //   sum U V = 65536 sum(Uh Vh) + 256 sum(Uh Vl + Ul Vh) + sum(Ul Vl):
 // four int8 MFMAs into three accumulators, combined in 64 bits and reduced once at the end.
 //
-// Grid: x = n*Q, y = ceil(Kp/32), z = ceil(Tp / (16*NTB)).
+// Grid: x = n*Q rounded up to a multiple of 8, y = ceil(Kp/32), z = ceil(Tp / (16*NTB)).  Workgroups are handed to the
+// 8 XCDs round-robin by linear id, so with gridDim.x a multiple of 8 all blocks of one x (which read the same V) share an L2.
 #pragma once
 #include "kernels_common.hpp"
 
@@ -25,6 +26,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
   constexpr int COLS = 16 * NTB;
   __shared__ uint32_t tile[32 * COLS * PL];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (blockIdx.x >= P.n * P.Q) return;             // grid.x is padded to a multiple of 8 (one XCD per x residue class)
   const int i = blockIdx.x / P.Q, q = blockIdx.x % P.Q;
   const int pt = 4 * q + wave;
   const int nkb = P.Kp >> 4, ntb = P.Tp >> 4, ncb = P.Cp >> 6;
@@ -113,14 +115,15 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
         }
       }
   __syncthreads();
-  uint32_t *Ob = O + ((size_t)i * P.Q + q) * P.Kp * P.Tp * PL;
+  uint32_t *Ob = O + ((size_t)i * P.Q + q) * P.Tp * PL;      // + k * (n*Q*Tp*PL): O is [Kp][n][Q][Tp][PL]
+  const size_t krow = (size_t)P.n * P.Q * P.Tp * PL;
   constexpr int ROWW = COLS * PL;   // words per tile row
 #pragma unroll
   for (int it = 0; it < (32 * ROWW) / 256; ++it) {
     const int e = it * 256 + threadIdx.x;
     const int row = e / ROWW, rem = e % ROWW;
     const int k = kb0 * 16 + row, tau = tb0 * 16 + rem / PL;
-    if (k < P.Kp && tau < P.T) Ob[((size_t)k * P.Tp + tb0 * 16) * PL + rem] = tile[e];   // padding tiles are neither written nor read
+    if (k < P.Kp && tau < P.T) Ob[(size_t)k * krow + (size_t)(tb0 * 16) * PL + rem] = tile[e];   // padding tiles are neither written nor read
   }
 }
 

@@ -28,6 +28,15 @@ struct KParams {
   int crt24;                  // every prod_{l != i} p_l is below 2^24: 24-bit multiplies suffice
 };
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by linear workgroup id.  For a grid
+// whose x extent is a multiple of 8, this maps block x to a work item such that each XCD gets one contiguous
+// chunk of the items: neighbours (which share input lines) then share an L2.  Items >= count are padding.
+__device__ __forceinline__ int xcd_chunked(int x, int gx, int count) {
+  const int per = gx >> 3;                 // blocks per XCD
+  const int item = (x & 7) * per + (x >> 3);
+  return item < count ? item : -1;
+}
+
 // ---- residues of 8-bit moduli -------------------------------------------------------------------
 
 // Residue of x modulo p for |x| < 2^24 and p <= 253, without division: q = rint(x/p) from one fused

@@ -15,7 +15,8 @@
 //
 //   U  [n][t*t][Kp/16][Cp/64][lane = (k%16) + 16*g][16 B]      (fragment-major: a wave reads 1 KiB runs)
 //   V  [n][t*t][Tp/16][Cp/64][tile%16][g][16 B]                 (fragment-major: 1 KiB per 16 tiles x 64 channels)
-//   O  [n][Q][Kp][Tp][4 B]      byte e of the last axis is transform point 4*q + e
+//   O  [Kp][n][Q][Tp][4 B]      byte e of the last axis is transform point 4*q + e; k outermost, so that the
+//                               n*Q words the inverse transform needs for one (k, tile) lie in one small region
 //
 // n moduli, t*t transform points, Cp = C rounded up to 64 (padding channels are
 // zero in U), Kp = K rounded up to 16, Tp = T rounded up to 16, Q = ceil(t*t/4).
@@ -53,8 +54,9 @@ RNSW_HD size_t v_offset(int slab, int tau, int c, int Tp, int Cp) {
   return frag * 1024 + (size_t)((tau & 15) * 64 + chan_pos64(c & 63));
 }
 
-RNSW_HD size_t o_offset(int i, int pt, int k, int tau, int Q, int Kp, int Tp) {
-  return ((((size_t)i * Q + (pt >> 2)) * Kp + k) * Tp + tau) * 4 + (pt & 3);
+RNSW_HD size_t o_offset(int i, int pt, int k, int tau, int n, int Q, int Kp, int Tp) {
+  (void)Kp;
+  return ((((size_t)k * n + i) * Q + (pt >> 2)) * Tp + tau) * 4 + (pt & 3);
 }
 
 RNSW_HD size_t u_offset_wide(int slab, int k, int c, int Kp, int Cp, int plane) {
@@ -70,8 +72,9 @@ RNSW_HD size_t v_offset_wide(int slab, int tau, int c, int Tp, int Cp, int plane
   return frag * 2048 + (size_t)plane * 1024 + (size_t)((tau & 15) * 64 + chan_pos64(c & 63));
 }
 
-RNSW_HD size_t o_offset_wide(int i, int pt, int k, int tau, int Q, int Kp, int Tp, int plane) {
-  return (((((size_t)i * Q + (pt >> 2)) * Kp + k) * Tp + tau) * 2 + plane) * 4 + (pt & 3);
+RNSW_HD size_t o_offset_wide(int i, int pt, int k, int tau, int n, int Q, int Kp, int Tp, int plane) {
+  (void)Kp;
+  return (((((size_t)k * n + i) * Q + (pt >> 2)) * Tp + tau) * 2 + plane) * 4 + (pt & 3);
 }
 
 }  // namespace rnswino

@@ -76,7 +76,10 @@ inline void launch(Kern kern, dim3 grid, hipStream_t st, Timing tm, Args... args
 // ---- K1 ----
 template <bool WIDE>
 void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
-  const dim3 grid((unsigned)(d.T * (d.Cp / 64)), (unsigned)d.n);
+  // x: multiple of 8 (see xcd_chunked()); y: one block per residue, or one block for all residues when there are
+  // enough units to fill the chip (the pixel gather is then done once instead of n times)
+  const long long units = (long long)d.T * (d.Cp / 64);
+  const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)(units >= 4096 ? 1 : d.n));
   switch (d.KS1) {
     case 1: launch(k1_input_transform<1, WIDE>, grid, st, tm, P, x, V); break;
     case 2: launch(k1_input_transform<2, WIDE>, grid, st, tm, P, x, V); break;
@@ -90,7 +93,8 @@ void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipS
 // in flight, limited by the register budget of the variant.
 template <int KS, int NTB, bool WIDE>
 void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
-  const dim3 grid((unsigned)(d.n * d.Q), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp / 16 + NTB - 1) / NTB));
+  // x padded to a multiple of 8 so that the blocks of one (residue, point group), which share V, run on one XCD
+  const dim3 grid((unsigned)((d.n * d.Q + 7) / 8 * 8), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp / 16 + NTB - 1) / NTB));
   launch(k2_residue_gemm<KS, NTB, WIDE>, grid, st, tm, P, U, V, O);
 }
 
@@ -324,8 +328,8 @@ int rnswino_debug_stage(const rnswino_plan_t *plan, int stage, const void *src_d
         for (int k = 0; k < d.K; ++k)
           for (int tau = 0; tau < d.T; ++tau)
             host_out[((size_t)slab * d.K + k) * d.T + tau] =
-                d.wide ? value(0, o_offset_wide(i, pt, k, tau, d.Q, d.Kp, d.Tp, 0), o_offset_wide(i, pt, k, tau, d.Q, d.Kp, d.Tp, 1))
-                       : value(o_offset(i, pt, k, tau, d.Q, d.Kp, d.Tp), 0, 0);
+                d.wide ? value(0, o_offset_wide(i, pt, k, tau, d.n, d.Q, d.Kp, d.Tp, 0), o_offset_wide(i, pt, k, tau, d.n, d.Q, d.Kp, d.Tp, 1))
+                       : value(o_offset(i, pt, k, tau, d.n, d.Q, d.Kp, d.Tp), 0, 0);
       }
     }
   }
