@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
           for (int u = 0; u < 4; ++u)
             acc[pl][u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], bf[cc][s][pl], acc[pl][u], 0, 0, 0);
       const int pt = 16 * cbk + (lane & 15);
-      int8_t *dst = V + ((((size_t)(i * P.P2 + pt) * (P.Tp >> 4) + (tau >> 4)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64 + g * 16;
+      int8_t *dst = V + ((((size_t)(tau >> 4) * (P.n * P.P2) + (i * P.P2 + pt)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64 + g * 16;
       if (WIDE) {
         // per plane |acc| <= t*t * 128 * 128 = 2^22, so 256 * acc_h + acc_l fits 32 bits
         v4i out_h, out_l;

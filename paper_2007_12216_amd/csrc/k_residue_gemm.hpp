@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
   if (pt < P.P2) {
     const int slab = i * P.P2 + pt;
     const int8_t *Ub = U + (size_t)slab * nkb * ncb * (1024 * PL) + lane * 16;
-    const int8_t *Vb = V + (size_t)slab * ntb * ncb * (1024 * PL) + (lane & 15) * 64 + (lane >> 4) * 16;
+    const int8_t *Vb = V + (size_t)slab * ncb * (1024 * PL) + (lane & 15) * 64 + (lane >> 4) * 16;   // + tile block * vstride
+    const size_t vstride = (size_t)P.n * P.P2 * ncb * (1024 * PL);
     for (int s0 = 0; s0 < ncb; s0 += KS) {
       v4i a[KS][2][PL], b[KS][NTB][PL];
 #pragma unroll
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
           for (int pl = 0; pl < PL; ++pl) {
             b[s][tb][pl] = (v4i){0, 0, 0, 0};
             if (tb0 + tb < ntb)
-              b[s][tb][pl] = *(const v4i *)(Vb + ((((size_t)(tb0 + tb) * ncb + s0 + s) * PL) + pl) * 1024);
+              b[s][tb][pl] = *(const v4i *)(Vb + (size_t)(tb0 + tb) * vstride + (size_t)((s0 + s) * PL + pl) * 1024);
           }
       }
 #pragma unroll

@@ -14,7 +14,8 @@
 // 4*g + j, and four accumulators u = b/4 cover the 64 channels).
 //
 //   U  [n][t*t][Kp/16][Cp/64][lane = (k%16) + 16*g][16 B]      (fragment-major: a wave reads 1 KiB runs)
-//   V  [n][t*t][Tp/16][Cp/64][tile%16][g][16 B]                 (fragment-major: 1 KiB per 16 tiles x 64 channels)
+//   V  [Tp/16][n][t*t][Cp/64][tile%16][g][16 B]                 (fragment-major: 1 KiB per 16 tiles x 64 channels;
+//                               tile block outermost, so that everything one tile produces lies in one region)
 //   O  [Kp][n][Q][Tp][4 B]      byte e of the last axis is transform point 4*q + e; k outermost, so that the
 //                               n*Q words the inverse transform needs for one (k, tile) lie in one small region
 //
@@ -49,8 +50,8 @@ RNSW_HD size_t u_offset(int slab, int k, int c, int Kp, int Cp) {
   return frag * 1024 + (size_t)(((k & 15) + 16 * g) * 16 + b);
 }
 
-RNSW_HD size_t v_offset(int slab, int tau, int c, int Tp, int Cp) {
-  const size_t frag = ((size_t)slab * (Tp >> 4) + (tau >> 4)) * (Cp >> 6) + (c >> 6);
+RNSW_HD size_t v_offset(int slab, int nslab, int tau, int c, int Cp) {
+  const size_t frag = ((size_t)(tau >> 4) * nslab + slab) * (Cp >> 6) + (c >> 6);
   return frag * 1024 + (size_t)((tau & 15) * 64 + chan_pos64(c & 63));
 }
 
@@ -67,8 +68,8 @@ RNSW_HD size_t u_offset_wide(int slab, int k, int c, int Kp, int Cp, int plane) 
   return frag * 2048 + (size_t)plane * 1024 + (size_t)(((k & 15) + 16 * g) * 16 + b);
 }
 
-RNSW_HD size_t v_offset_wide(int slab, int tau, int c, int Tp, int Cp, int plane) {
-  const size_t frag = ((size_t)slab * (Tp >> 4) + (tau >> 4)) * (Cp >> 6) + (c >> 6);
+RNSW_HD size_t v_offset_wide(int slab, int nslab, int tau, int c, int Cp, int plane) {
+  const size_t frag = ((size_t)(tau >> 4) * nslab + slab) * (Cp >> 6) + (c >> 6);
   return frag * 2048 + (size_t)plane * 1024 + (size_t)((tau & 15) * 64 + chan_pos64(c & 63));
 }
 

@@ -322,8 +322,8 @@ int rnswino_debug_stage(const rnswino_plan_t *plan, int stage, const void *src_d
         for (int tau = 0; tau < d.T; ++tau)
           for (int c = 0; c < d.C; ++c)
             host_out[((size_t)slab * d.T + tau) * d.C + c] =
-                d.wide ? value(0, v_offset_wide(slab, tau, c, d.Tp, d.Cp, 0), v_offset_wide(slab, tau, c, d.Tp, d.Cp, 1))
-                       : value(v_offset(slab, tau, c, d.Tp, d.Cp), 0, 0);
+                d.wide ? value(0, v_offset_wide(slab, d.n * d.P2, tau, c, d.Cp, 0), v_offset_wide(slab, d.n * d.P2, tau, c, d.Cp, 1))
+                       : value(v_offset(slab, d.n * d.P2, tau, c, d.Cp), 0, 0);
       } else {
         for (int k = 0; k < d.K; ++k)
           for (int tau = 0; tau < d.T; ++tau)
