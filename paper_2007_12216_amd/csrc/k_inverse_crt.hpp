@@ -30,7 +30,19 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
   if (wave >= P.RB3) return;
   const int ntb = P.Tp >> 4;
-  const int k = blockIdx.x / ntb, tb = blockIdx.x % ntb;
+  // Workgroups go to the 8 XCDs round-robin by id.  Two neighbouring tile blocks of one k share a 128-byte line of
+  // O, so the tile blocks of a k are given ids that differ by multiples of 8: one L2 fetches each line once.
+  int k, tb;
+  {
+    const int id = blockIdx.x, full = (P.K >> 3) * 8 * ntb;   // ids covering the k's below the last multiple of 8
+    if (id < full) {
+      tb = (id >> 3) % ntb;
+      k = (id & 7) + 8 * (id / (8 * ntb));
+    } else {
+      k = (P.K >> 3) * 8 + (id - full) / ntb;
+      tb = (id - full) % ntb;
+    }
+  }
   const int tau = tb * 16 + (lane & 15);
 
   v4i of[NRES][KS3][PL];
