@@ -31,6 +31,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
+# (profiles/conv2d_config2_hbm_traffic.md).  Counters cannot be read from inside this script, so the figures are
+# recorded here for the workload they were taken on; other workloads report null.
+MEASURED_TRAFFIC_BYTES = {2: {"input_transform": 7.75e6, "residue_gemm": 38.60e6, "inverse_transform_mrc": 10.14e6}}
 ROTATION_BYTES = 640 << 20      # operands cycled through in the cold loop (> 256 MB Infinity Cache + 32 MB L2)
 
 
@@ -169,7 +173,8 @@ def main():
     dominant = max(names, key=lambda nm: stage_ms[nm])
     achieved = bytes_per[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant),
                 "algorithmic_bytes": bytes_per[dominant],
                 "stage_us": {nm: round(stage_ms[nm] * 1e3, 2) for nm in names},
                 "stage_GBps": {nm: round(bytes_per[nm] / (stage_ms[nm] * 1e-3) / 1e9, 1) for nm in names}}
