@@ -3,7 +3,8 @@
 // int8 operands on v_mfma_i32_16x16x64_i8, int32 accumulation.
 //
 // Block = 4 waves = the 4 transform points of one group q (they end up as the 4 bytes of one O word); every
-// wave computes a 32 (k) x 16*NTB (tile) block of its point over the whole of C.  Operand fragments are read
+// wave computes a 16*RM (k) x 16*NTB (tile) block of its point over the whole of C (RM = 2, or 4 on layers large
+// enough to fill the chip with the bigger blocks: each V fragment then feeds four MFMAs instead of two).  Operand fragments are read
 // straight from global memory in 1 KiB runs (layout.hpp); KS contraction steps are loaded before any is
 // consumed.  The four results of a group are exchanged through LDS so that O is written as whole words.
 //
@@ -11,34 +12,35 @@
 //   sum U V = 65536 sum(Uh Vh) + 256 sum(Uh Vl + Ul Vh) + sum(Ul Vl):
 // four int8 MFMAs into three accumulators, combined in 64 bits and reduced once at the end.
 //
-// Grid: x = n*Q rounded up to a multiple of 8, y = ceil(Kp/32), z = ceil(Tp / (16*NTB)).  Workgroups are handed to the
+// Grid: x = n*Q rounded up to a multiple of 8, y = ceil(Kp / (16*RM)), z = ceil(Tp / (16*NTB)).  Workgroups are handed to the
 // 8 XCDs round-robin by linear id, so with gridDim.x a multiple of 8 all blocks of one x (which read the same V) share an L2.
 #pragma once
 #include "kernels_common.hpp"
 
 namespace rnswino {
 
-template <int KS, int NTB, bool WIDE>
+template <int KS, int NTB, int RM, bool WIDE>
 __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *__restrict__ U,
                                                         const int8_t *__restrict__ V, uint32_t *__restrict__ O) {
   constexpr int PL = WIDE ? 2 : 1;
   constexpr int NACC = WIDE ? 3 : 1;
   constexpr int COLS = 16 * NTB;
-  __shared__ uint32_t tile[32 * COLS * PL];
+  constexpr int ROWS = 16 * RM;          // k rows per wave and per block
+  __shared__ uint32_t tile[ROWS * COLS * PL];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (blockIdx.x >= P.n * P.Q) return;             // grid.x is padded to a multiple of 8 (one XCD per x residue class)
   const int i = blockIdx.x / P.Q, q = blockIdx.x % P.Q;
   const int pt = 4 * q + wave;
   const int nkb = P.Kp >> 4, ntb = P.Tp >> 4, ncb = P.Cp >> 6;
-  const int kb0 = blockIdx.y * 2, tb0 = blockIdx.z * NTB;
+  const int kb0 = blockIdx.y * RM, tb0 = blockIdx.z * NTB;
   const int p = P.p[i];
   const float inv = P.inv_p[i];
 
-  v4i acc[NACC][2][NTB];
+  v4i acc[NACC][RM][NTB];
 #pragma unroll
   for (int a = 0; a < NACC; ++a)
 #pragma unroll
-    for (int rm = 0; rm < 2; ++rm)
+    for (int rm = 0; rm < RM; ++rm)
 #pragma unroll
       for (int tb = 0; tb < NTB; ++tb) acc[a][rm][tb] = (v4i){0, 0, 0, 0};
 
@@ -48,11 +50,11 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
     const int8_t *Vb = V + (size_t)slab * ncb * (1024 * PL) + (lane & 15) * 64 + (lane >> 4) * 16;   // + tile block * vstride
     const size_t vstride = (size_t)P.n * P.P2 * ncb * (1024 * PL);
     for (int s0 = 0; s0 < ncb; s0 += KS) {
-      v4i a[KS][2][PL], b[KS][NTB][PL];
+      v4i a[KS][RM][PL], b[KS][NTB][PL];
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
 #pragma unroll
-        for (int rm = 0; rm < 2; ++rm)
+        for (int rm = 0; rm < RM; ++rm)
 #pragma unroll
           for (int pl = 0; pl < PL; ++pl) {
             a[s][rm][pl] = (v4i){0, 0, 0, 0};
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
 #pragma unroll
       for (int s = 0; s < KS; ++s)
 #pragma unroll
-        for (int rm = 0; rm < 2; ++rm)
+        for (int rm = 0; rm < RM; ++rm)
 #pragma unroll
           for (int tb = 0; tb < NTB; ++tb) {
             if (WIDE) {
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
       // |acc| < 2^24.  (Byte planes need nothing here: a step adds at most 2^21 and C is below 2^14.)
       if (!WIDE && (((s0 + KS) & 7) == 0) && (s0 + KS < ncb)) {
 #pragma unroll
-        for (int rm = 0; rm < 2; ++rm)
+        for (int rm = 0; rm < RM; ++rm)
 #pragma unroll
           for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
 
   uint8_t *tile8 = (uint8_t *)tile;
 #pragma unroll
-  for (int rm = 0; rm < 2; ++rm)
+  for (int rm = 0; rm < RM; ++rm)
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
   const size_t krow = (size_t)P.n * P.Q * P.Tp * PL;
   constexpr int ROWW = COLS * PL;   // words per tile row
 #pragma unroll
-  for (int it = 0; it < (32 * ROWW) / 256; ++it) {
+  for (int it = 0; it < (ROWS * ROWW) / 256; ++it) {
     const int e = it * 256 + threadIdx.x;
     const int row = e / ROWW, rem = e % ROWW;
     const int k = kb0 * 16 + row, tau = tb0 * 16 + rem / PL;

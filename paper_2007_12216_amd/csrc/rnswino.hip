@@ -91,20 +91,30 @@ void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipS
 // ---- K2 ----
 // NTB = 16-tile column blocks per wave (1, 2 or 4, the smallest that covers Tp up to 64); KS = contraction steps
 // in flight, limited by the register budget of the variant.
-template <int KS, int NTB, bool WIDE>
+template <int KS, int NTB, int RM, bool WIDE>
 void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
   // x padded to a multiple of 8 so that the blocks of one (residue, point group), which share V, run on one XCD
-  const dim3 grid((unsigned)((d.n * d.Q + 7) / 8 * 8), (unsigned)((d.Kp + 31) / 32), (unsigned)((d.Tp / 16 + NTB - 1) / NTB));
-  launch(k2_residue_gemm<KS, NTB, WIDE>, grid, st, tm, P, U, V, O);
+  const dim3 grid((unsigned)((d.n * d.Q + 7) / 8 * 8), (unsigned)((d.Kp + 16 * RM - 1) / (16 * RM)),
+                  (unsigned)((d.Tp / 16 + NTB - 1) / NTB));
+  launch(k2_residue_gemm<KS, NTB, RM, WIDE>, grid, st, tm, P, U, V, O);
 }
 
 template <int NTB, bool WIDE>
 void launch_k2_ntb(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
   const int ncb = d.Cp / 64;
+  // 64 rows per wave when K is large (V re-reads dominate) and that still leaves >= 4 blocks per CU; measured on the
+  // VGG16 stack this wins for K >= 256 and loses for K <= 128 (8-bit moduli, full-width tiles only: the register
+  // budget of the other variants is spent on their extra accumulators)
+  const long long big_blocks = (long long)((d.n * d.Q + 7) / 8 * 8) * ((d.Kp + 63) / 64) * ((d.Tp / 16 + NTB - 1) / NTB);
+  if (!WIDE && NTB == 4 && d.Kp >= 256 && big_blocks >= 1024) {
+    if (ncb % 2 == 0) launch_k2_one<2, NTB, (WIDE || NTB != 4) ? 2 : 4, WIDE>(d, P, U, V, O, st, tm);
+    else launch_k2_one<1, NTB, (WIDE || NTB != 4) ? 2 : 4, WIDE>(d, P, U, V, O, st, tm);
+    return;
+  }
   constexpr int KSMAX = WIDE ? (NTB == 1 ? 4 : NTB == 2 ? 2 : 1) : 4;
-  if (KSMAX >= 4 && ncb % 4 == 0) launch_k2_one<4, NTB, WIDE>(d, P, U, V, O, st, tm);
-  else if (KSMAX >= 2 && ncb % 2 == 0) launch_k2_one<2, NTB, WIDE>(d, P, U, V, O, st, tm);
-  else launch_k2_one<1, NTB, WIDE>(d, P, U, V, O, st, tm);
+  if (KSMAX >= 4 && ncb % 4 == 0) launch_k2_one<4, NTB, 2, WIDE>(d, P, U, V, O, st, tm);
+  else if (KSMAX >= 2 && ncb % 2 == 0) launch_k2_one<2, NTB, 2, WIDE>(d, P, U, V, O, st, tm);
+  else launch_k2_one<1, NTB, 2, WIDE>(d, P, U, V, O, st, tm);
 }
 
 template <bool WIDE>
