@@ -119,6 +119,16 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
                    int32_t *y_dev, void *workspace_dev, void *stream);
 
 /*
+ * rnswino_conv2d fused with the layer glue of rnswino_requant_pool: the inverse-transform kernel writes
+ *   a = clamp(floor(y / 2^shift), -128, 127)   (int8 [N][K][Ho][Wo]), after a 2x2 stride-2 max-pool when pool != 0
+ * (int8 [N][K][Ho/2][Wo/2]), and the int32 y is never stored.  Supported when m is 4 or 8, Wo is a multiple of 4, and,
+ * for pooling, Ho and Wo are even; otherwise RNSWINO_E_UNSUPPORTED (use rnswino_conv2d + rnswino_requant_pool).
+ * a_dev must be 4-byte aligned.  Not part of the paper's method (the 13-layer stack workload needs it).
+ */
+int rnswino_conv2d_requant(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int8_t *a_dev,
+                           int32_t shift, int32_t pool, void *workspace_dev, void *stream);
+
+/*
  * rnswino_conv2d with six caller-created hipEvent_t (passed as void*): events[2j] and events[2j+1] receive the
  * start and stop timestamps of kernel j (0: input transform, 1: residue GEMM, 2: inverse transform + conversion),
  * so hipEventElapsedTime(events[2j], events[2j+1]) is that kernel's own duration.  For per-stage measurement

@@ -15,7 +15,8 @@ FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY = 1, 2
 
 EXPORTED_SYMBOLS = (
     "rnswino_plan", "rnswino_plan_destroy", "rnswino_output_dims", "rnswino_filter_bytes",
-    "rnswino_workspace_bytes", "rnswino_filter_transform", "rnswino_conv2d", "rnswino_conv2d_events",
+    "rnswino_workspace_bytes", "rnswino_filter_transform", "rnswino_conv2d", "rnswino_conv2d_requant",
+    "rnswino_conv2d_events",
     "rnswino_requant_pool",
     "rnswino_plan_get_matrix", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
     "rnswino_debug_stage", "rnswino_strerror",
@@ -65,6 +66,8 @@ def lib():
         L.rnswino_filter_transform.restype = ctypes.c_int
         L.rnswino_conv2d.argtypes = [vp, vp, vp, vp, vp, vp]
         L.rnswino_conv2d.restype = ctypes.c_int
+        L.rnswino_conv2d_requant.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
+        L.rnswino_conv2d_requant.restype = ctypes.c_int
         L.rnswino_conv2d_events.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
         L.rnswino_conv2d_events.restype = ctypes.c_int
         L.rnswino_requant_pool.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp]
@@ -160,6 +163,11 @@ def rnswino_filter_transform(plan: Plan, w_dev, U_dev, stream: int = 0) -> None:
 def rnswino_conv2d(plan: Plan, x_dev, U_dev, y_dev, workspace_dev, stream: int = 0) -> None:
     _check(lib().rnswino_conv2d(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev), _ptr(workspace_dev), stream),
            "rnswino_conv2d")
+
+
+def rnswino_conv2d_requant(plan: Plan, x_dev, U_dev, a_dev, shift: int, pool: bool, workspace_dev, stream: int = 0) -> None:
+    _check(lib().rnswino_conv2d_requant(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(a_dev), shift, int(bool(pool)),
+                                        _ptr(workspace_dev), stream), "rnswino_conv2d_requant")
 
 
 def rnswino_conv2d_events(plan: Plan, x_dev, U_dev, y_dev, workspace_dev, stream: int, events) -> None:

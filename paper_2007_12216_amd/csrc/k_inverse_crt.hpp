@@ -120,6 +120,31 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
       val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
     }
     const int o0 = 16 * rb + 4 * g;
+    if (P.epi != 0) {
+      // Fused glue for chained layers (host guarantees m in {4, 8}, Wo % 4 == 0, even Ho and Wo when pooling):
+      // a = clamp(y >> shift, -128, 127); the shift is monotone, so it commutes with the max of the pool.
+      const int u = (int)(((float)o0 + 0.5f) * inv_m);
+      const int v = o0 - u * m;
+      const int oy = ty * m + u, ox = tx * m + v;
+      if (P.epi == 1) {
+        uint32_t packed = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) packed |= ((uint32_t)min(127, max(-128, val[j] >> P.shift)) & 0xFFu) << (8 * j);
+        int8_t *aplane = P.act + ((size_t)img * P.K + k) * P.Ho * P.Wo;
+        if (tile_ok && o0 < mm && oy < P.Ho && ox < P.Wo) *(uint32_t *)(aplane + (size_t)oy * P.Wo + ox) = packed;
+      } else {
+        // rows u and u+1 (u even) of an output tile sit in lanes l and l ^ 4m (m = 8: 32 apart, m = 4: 16 apart)
+        const int h0 = max(val[0], val[1]), h1 = max(val[2], val[3]);
+        const int delta = 4 * m;
+        const int o0p = __shfl_xor(h0, delta), o1p = __shfl_xor(h1, delta);
+        const int p0 = min(127, max(-128, max(h0, o0p) >> P.shift)), p1 = min(127, max(-128, max(h1, o1p) >> P.shift));
+        const int Hq = P.Ho >> 1, Wq = P.Wo >> 1;
+        int8_t *aplane = P.act + ((size_t)img * P.K + k) * Hq * Wq;
+        if (tile_ok && o0 < mm && (u & 1) == 0 && oy < P.Ho && ox < P.Wo)
+          *(uint16_t *)(aplane + (size_t)(oy >> 1) * Wq + (ox >> 1)) = (uint16_t)(((uint32_t)p0 & 0xFFu) | (((uint32_t)p1 & 0xFFu) << 8));
+      }
+      continue;
+    }
     if (!tile_ok || o0 >= mm) continue;
     if (vec4) {
       const int u = (int)(((float)o0 + 0.5f) * inv_m);

@@ -26,6 +26,10 @@ struct KParams {
   uint32_t crt_c[8];          // prod_{l != i} p_l mod 2^32
   uint32_t prod_mod32;        // prod p_i mod 2^32
   int crt24;                  // every prod_{l != i} p_l is below 2^24: 24-bit multiplies suffice
+  // fused re-quantisation in the inverse-transform kernel (chained layers): 0 = store int32 y,
+  // 1 = store int8 clamp(y >> shift), 2 = the same after a 2x2 stride-2 max-pool
+  int epi, shift;
+  int8_t *act;                // int8 output of modes 1 and 2
 };
 
 // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by linear workgroup id.  For a grid

@@ -151,13 +151,18 @@ void launch_k3(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, h
   }
 }
 
+// epi: 0 = int32 y_dev; 1 / 2 = int8 act_dev after shift/clamp (/ and 2x2 max-pool)
 int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
-                void *workspace_dev, void *stream, void *const *events) {
-  if (!plan || !x_dev || !U_dev || !y_dev || !workspace_dev) return RNSWINO_E_INVALID;
+                void *workspace_dev, void *stream, void *const *events, int epi = 0, int shift = 0,
+                int8_t *act_dev = nullptr) {
+  if (!plan || !x_dev || !U_dev || !workspace_dev) return RNSWINO_E_INVALID;
+  if (epi == 0 ? !y_dev : !act_dev) return RNSWINO_E_INVALID;
   if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
   if (((uintptr_t)U_dev | (uintptr_t)workspace_dev | (uintptr_t)y_dev) & 15) return RNSWINO_E_INVALID;
+  if ((uintptr_t)act_dev & 3) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
-  const KParams P = make_params(plan);
+  KParams P = make_params(plan);
+  P.epi = epi; P.shift = shift; P.act = act_dev;
   hipStream_t st = (hipStream_t)stream;
   int8_t *Vp = (int8_t *)workspace_dev;
   uint32_t *Op = (uint32_t *)((char *)workspace_dev + align256(v_bytes(d)));
@@ -262,6 +267,14 @@ int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, vo
 int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,
                    void *workspace_dev, void *stream) {
   return conv2d_impl(plan, x_dev, U_dev, y_dev, workspace_dev, stream, nullptr);
+}
+
+int rnswino_conv2d_requant(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int8_t *a_dev,
+                           int32_t shift, int32_t pool, void *workspace_dev, void *stream) {
+  if (!plan || shift < 0 || shift > 31) return RNSWINO_E_INVALID;
+  const Dims &d = plan->dims;
+  if ((d.m != 4 && d.m != 8) || (d.Wo & 3) || (pool && ((d.Ho | d.Wo) & 1))) return RNSWINO_E_UNSUPPORTED;
+  return conv2d_impl(plan, x_dev, U_dev, nullptr, workspace_dev, stream, nullptr, pool ? 2 : 1, shift, a_dev);
 }
 
 int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev,

@@ -40,14 +40,20 @@ class ConvStack:
             self.w.append(wd)
             B.rnswino_filter_transform(p, wd, U, self._stream())
 
-    def forward(self, x: torch.Tensor, keep_last_y: bool = False):
+    def forward(self, x: torch.Tensor, keep_last_y: bool = False, fuse: bool = True):
         """x: int8 [N][C][H][W] of the first layer.  Returns the int8 activations of the last layer
-        (and its raw int32 output if asked)."""
+        (and its raw int32 output if asked).  With fuse=True the re-quantisation (and pooling) runs inside the
+        inverse-transform kernel wherever the library supports it."""
         st = self._stream()
         a = x
-        for l, p, U, out in zip(self.cfg, self.plans, self.U, self.act):
-            B.rnswino_conv2d(p, a, U, self.y, self.workspace, st)
-            B.rnswino_requant_pool(self.y, out, l["N"] * l["K"], p.Ho, p.Wo, l["shift"], l["pool"], st)
+        last = len(self.cfg) - 1
+        for li, (l, p, U, out) in enumerate(zip(self.cfg, self.plans, self.U, self.act)):
+            fusable = p.m in (4, 8) and p.Wo % 4 == 0 and (not l["pool"] or (p.Ho % 2 == 0 and p.Wo % 2 == 0))
+            if fuse and fusable and not (keep_last_y and li == last):
+                B.rnswino_conv2d_requant(p, a, U, out, l["shift"], l["pool"], self.workspace, st)
+            else:
+                B.rnswino_conv2d(p, a, U, self.y, self.workspace, st)
+                B.rnswino_requant_pool(self.y, out, l["N"] * l["K"], p.Ho, p.Wo, l["shift"], l["pool"], st)
             a = out
         if keep_last_y:
             p = self.plans[-1]

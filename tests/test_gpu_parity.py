@@ -149,8 +149,8 @@ def oracle_stack(layers, x, weights):
     return acts, y
 
 
-@pytest.mark.parametrize("batch,hw", [(2, 32), (1, 48)])
-def test_vgg16_stack_reduced_plane(batch, hw):
+@pytest.mark.parametrize("batch,hw,fuse", [(2, 32, True), (1, 48, True), (2, 32, False)])
+def test_vgg16_stack_reduced_plane(batch, hw, fuse):
     from paper_2007_12216_amd.stack import ConvStack
     print("stack", batch, hw, flush=True)
     layers = si.vgg16_stack(batch=batch, hw=hw)
@@ -158,12 +158,16 @@ def test_vgg16_stack_reduced_plane(batch, hw):
     x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
     stack = ConvStack(layers)
     stack.set_weights(weights)
-    a, y = stack.forward(torch.from_numpy(x).to("cuda:0"), keep_last_y=True)
+    a, y = stack.forward(torch.from_numpy(x).to("cuda:0"), keep_last_y=True, fuse=fuse)
     torch.cuda.synchronize()
     ref_acts, ref_y = oracle_stack(layers, x, weights)
     for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
         assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
     assert np.array_equal(y.cpu().numpy(), ref_y)
+    if fuse:   # and with the last layer fused as well
+        a2 = stack.forward(torch.from_numpy(x).to("cuda:0"))
+        torch.cuda.synchronize()
+        assert np.array_equal(a2.cpu().numpy(), ref_acts[-1])
     # the re-quantisation keeps the activations alive: neither all zero nor all saturated
     last = ref_acts[-1].astype(np.int32)
     assert (last != 0).mean() > 0.5 and (np.abs(last) >= 127).mean() < 0.5
@@ -185,3 +189,33 @@ def test_vgg16_stack_full_size():
     for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
         assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
     assert np.array_equal(y.cpu().numpy(), ref_y)
+
+
+@pytest.mark.parametrize("m,pool", [(8, False), (8, True), (4, False), (4, True)])
+def test_fused_requant_matches_the_oracle_glue(m, pool):
+    from oracle import requant_shift_clamp, maxpool2x2
+    print("fused requant", m, pool, flush=True)
+    N, C, K, H, W, r, pad, moduli, shift = 2, 20, 24, 20, 28, 3, 1, (251, 241, 239), 10
+    x = si.int8_tensor(401, (N, C, H, W))
+    w = si.int8_tensor(402, (K, C, r, r))
+    from paper_2007_12216_amd.layer import ConvLayer
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli)
+    layer.set_weights(w)
+    shape = (N, K, H // 2, W // 2) if pool else (N, K, H, W)
+    a = torch.empty(shape, dtype=torch.int8, device="cuda:0")
+    rn.rnswino_conv2d_requant(layer.plan, torch.from_numpy(x).to("cuda:0"), layer.U, a, shift, pool, layer.workspace,
+                              torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ref = requant_shift_clamp(direct_conv2d(x, w, pad), shift)
+    if pool:
+        ref = maxpool2x2(ref)
+    assert np.array_equal(a.cpu().numpy(), ref)
+
+
+def test_fused_requant_refuses_unsupported_tiles():
+    from paper_2007_12216_amd.layer import ConvLayer
+    layer = ConvLayer(1, 4, 4, 12, 12, 3, 10, 1, (253, 251, 247))
+    a = torch.empty((1, 4, 12, 12), dtype=torch.int8, device="cuda:0")
+    with pytest.raises(rn.RnsWinoError) as e:
+        rn.rnswino_conv2d_requant(layer.plan, a, layer.U, a, 9, False, layer.workspace, 0)
+    assert e.value.code == -2
