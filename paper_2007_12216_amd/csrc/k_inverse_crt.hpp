@@ -22,6 +22,74 @@
 
 namespace rnswino {
 
+
+// CRT conversion of the four outputs of one lane (row block rb, lane group g) and their store: int32 y, or, for
+// chained layers, int8 clamp(y >> shift) with an optional 2x2 max-pool (the shift is monotone, so it commutes with
+// the max).  Must be called by all lanes of a wave (the pooled mode exchanges rows between lanes).
+template <int NRES>
+__device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uint32_t (&w)[NRES][4], int rb, int g,
+                                                     int k, int tau, int32_t *__restrict__ y) {
+  int val[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t sum = 0;
+    double fs = 0.0;
+#pragma unroll
+    for (int i = 0; i < NRES; ++i) {
+      sum += P.crt24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
+      fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
+    }
+    const int kk = __double2int_rn(fs);
+    val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+  }
+  const int m = P.m, mm = m * m;
+  const bool tile_ok = tau < P.T;
+  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
+  const float inv_m = 1.0f / (float)m;
+  const int o0 = 16 * rb + 4 * g;
+  if (P.epi != 0) {
+    // host guarantees m in {4, 8}, Wo % 4 == 0, even Ho and Wo when pooling
+    const int u = (int)(((float)o0 + 0.5f) * inv_m);
+    const int v = o0 - u * m;
+    const int oy = ty * m + u, ox = tx * m + v;
+    if (P.epi == 1) {
+      uint32_t packed = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) packed |= ((uint32_t)min(127, max(-128, val[j] >> P.shift)) & 0xFFu) << (8 * j);
+      int8_t *aplane = P.act + ((size_t)img * P.K + k) * P.Ho * P.Wo;
+      if (tile_ok && o0 < mm && oy < P.Ho && ox < P.Wo) *(uint32_t *)(aplane + (size_t)oy * P.Wo + ox) = packed;
+    } else {
+      // rows u and u+1 (u even) of an output tile sit in lanes l and l ^ 4m (m = 8: 32 apart, m = 4: 16 apart)
+      const int h0 = max(val[0], val[1]), h1 = max(val[2], val[3]);
+      const int delta = 4 * m;
+      const int o0p = __shfl_xor(h0, delta), o1p = __shfl_xor(h1, delta);
+      const int p0 = min(127, max(-128, max(h0, o0p) >> P.shift)), p1 = min(127, max(-128, max(h1, o1p) >> P.shift));
+      const int Hq = P.Ho >> 1, Wq = P.Wo >> 1;
+      int8_t *aplane = P.act + ((size_t)img * P.K + k) * Hq * Wq;
+      if (tile_ok && o0 < mm && (u & 1) == 0 && oy < P.Ho && ox < P.Wo)
+        *(uint16_t *)(aplane + (size_t)(oy >> 1) * Wq + (ox >> 1)) = (uint16_t)(((uint32_t)p0 & 0xFFu) | (((uint32_t)p1 & 0xFFu) << 8));
+    }
+    return;
+  }
+  if (!tile_ok || o0 >= mm) return;
+  int32_t *yplane = y + ((size_t)img * P.K + k) * P.Ho * P.Wo;
+  if (((m & 3) == 0) && ((P.Wo & 3) == 0)) {   // four consecutive outputs stay in one row, 16-byte aligned
+    const int u = (int)(((float)o0 + 0.5f) * inv_m);
+    const int v = o0 - u * m;
+    const int oy = ty * m + u, ox = tx * m + v;
+    if (oy < P.Ho && ox < P.Wo) *(v4i *)(yplane + (size_t)oy * P.Wo + ox) = (v4i){val[0], val[1], val[2], val[3]};
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int o = o0 + j;
+      const int u = (int)(((float)o + 0.5f) * inv_m);
+      const int v = o - u * m;
+      const int oy = ty * m + u, ox = tx * m + v;
+      if (o < mm && oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val[j];
+    }
+  }
+}
+
 template <int NRES, int KS3, bool WIDE>
 __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t *__restrict__ O,
                                                        int32_t *__restrict__ y) {
@@ -65,13 +133,6 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
         }
       }
 
-  const int m = P.m, mm = m * m;
-  const bool tile_ok = tau < P.T;
-  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
-  int32_t *yplane = y + ((size_t)img * P.K + k) * P.Ho * P.Wo;
-  const float inv_m = 1.0f / (float)m;
-  const bool vec4 = ((m & 3) == 0) && ((P.Wo & 3) == 0);   // four consecutive outputs stay in one row, 16-byte aligned
-
   for (int rb = wave; rb < P.RB3; rb += 4) {
     uint32_t w[NRES][4];
 #pragma unroll
@@ -106,63 +167,77 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
         }
       }
     }
-    int val[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint32_t sum = 0;
-      double fs = 0.0;
-#pragma unroll
-      for (int i = 0; i < NRES; ++i) {
-        sum += P.crt24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
-        fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
-      }
-      const int kk = __double2int_rn(fs);
-      val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
-    }
-    const int o0 = 16 * rb + 4 * g;
-    if (P.epi != 0) {
-      // Fused glue for chained layers (host guarantees m in {4, 8}, Wo % 4 == 0, even Ho and Wo when pooling):
-      // a = clamp(y >> shift, -128, 127); the shift is monotone, so it commutes with the max of the pool.
-      const int u = (int)(((float)o0 + 0.5f) * inv_m);
-      const int v = o0 - u * m;
-      const int oy = ty * m + u, ox = tx * m + v;
-      if (P.epi == 1) {
-        uint32_t packed = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) packed |= ((uint32_t)min(127, max(-128, val[j] >> P.shift)) & 0xFFu) << (8 * j);
-        int8_t *aplane = P.act + ((size_t)img * P.K + k) * P.Ho * P.Wo;
-        if (tile_ok && o0 < mm && oy < P.Ho && ox < P.Wo) *(uint32_t *)(aplane + (size_t)oy * P.Wo + ox) = packed;
-      } else {
-        // rows u and u+1 (u even) of an output tile sit in lanes l and l ^ 4m (m = 8: 32 apart, m = 4: 16 apart)
-        const int h0 = max(val[0], val[1]), h1 = max(val[2], val[3]);
-        const int delta = 4 * m;
-        const int o0p = __shfl_xor(h0, delta), o1p = __shfl_xor(h1, delta);
-        const int p0 = min(127, max(-128, max(h0, o0p) >> P.shift)), p1 = min(127, max(-128, max(h1, o1p) >> P.shift));
-        const int Hq = P.Ho >> 1, Wq = P.Wo >> 1;
-        int8_t *aplane = P.act + ((size_t)img * P.K + k) * Hq * Wq;
-        if (tile_ok && o0 < mm && (u & 1) == 0 && oy < P.Ho && ox < P.Wo)
-          *(uint16_t *)(aplane + (size_t)(oy >> 1) * Wq + (ox >> 1)) = (uint16_t)(((uint32_t)p0 & 0xFFu) | (((uint32_t)p1 & 0xFFu) << 8));
-      }
-      continue;
-    }
-    if (!tile_ok || o0 >= mm) continue;
-    if (vec4) {
-      const int u = (int)(((float)o0 + 0.5f) * inv_m);
-      const int v = o0 - u * m;
-      const int oy = ty * m + u, ox = tx * m + v;
-      if (oy < P.Ho && ox < P.Wo) *(v4i *)(yplane + (size_t)oy * P.Wo + ox) = (v4i){val[0], val[1], val[2], val[3]};
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int o = o0 + j;
-        const int u = (int)(((float)o + 0.5f) * inv_m);
-        const int v = o - u * m;
-        const int oy = ty * m + u, ox = tx * m + v;
-        if (o < mm && oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val[j];
-      }
-    }
+    k3_convert_and_store<NRES>(P, w, rb, g, k, tau, y);
   }
 }
 
+
+
+// Streaming variant for layers with many tiles (8-bit moduli, table of all residues <= 64 KiB): the table is staged
+// once per block in LDS, and every wave walks over units = (k, block of 16 tiles) with a grid stride, loading the O
+// operand of its next unit while the current one is multiplied and converted.  Per unit a wave issues only its own
+// O loads (no table reads from global memory, no copies of O in other waves); the table fragments come from LDS.
+// Grid: min(ceil(units / 4), K3_STREAM_BLOCKS) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
+constexpr int K3_STREAM_BLOCKS = 1024;
+
+template <int NRES, int KS3>
+__global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const uint32_t *__restrict__ O,
+                                                              int32_t *__restrict__ y) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t ka_lds[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int ntb = P.Tp >> 4;
+  const long long nunits = (long long)P.K * ntb;
+  const long long nwaves = (long long)gridDim.x * 4;
+  {
+    const int bytes = NRES * P.RB3 * KS3 * 1024;
+    for (int off = threadIdx.x * 16; off < bytes; off += 256 * 16) *(v4i *)(ka_lds + off) = *(const v4i *)(P.KA + off);
+  }
+  __syncthreads();
+  long long unit = (long long)blockIdx.x * 4 + wave;
+  if (unit >= nunits) return;
+
+  auto load_o = [&](long long u, v4i (&of)[NRES][KS3]) {
+    const int k = (int)(u / ntb), tau = (int)(u % ntb) * 16 + (lane & 15);
+#pragma unroll
+    for (int i = 0; i < NRES; ++i)
+#pragma unroll
+      for (int s = 0; s < KS3; ++s)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int q = 16 * s + 4 * g + e;
+          of[i][s][e] = (q < P.Q && tau < P.T) ? (int)O[((((size_t)k * P.n + i) * P.Q + q) * P.Tp + tau)] : 0;
+        }
+  };
+
+  v4i cur[NRES][KS3], nxt[NRES][KS3];
+  load_o(unit, cur);
+  for (; unit < nunits; unit += nwaves) {
+    const bool more = unit + nwaves < nunits;
+    if (more) load_o(unit + nwaves, nxt);
+    const int k = (int)(unit / ntb), tau = (int)(unit % ntb) * 16 + (lane & 15);
+    for (int rb = 0; rb < P.RB3; ++rb) {
+      uint32_t w[NRES][4];
+#pragma unroll
+      for (int i = 0; i < NRES; ++i) {
+        v4i acc = (v4i){0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < KS3; ++s) {
+          const v4i a = *(const v4i *)(ka_lds + (((i * P.RB3 + rb) * KS3) + s) * 1024 + lane * 16);
+          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, cur[i][s], acc, 0, 0, 0);
+        }
+        // |acc| <= t*t * 126 * 127 < 2^24; residue shifted by +p so that it is non-negative
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[i][j] = (uint32_t)(mod_near(acc[j], P.inv_p[i], P.p[i]) + P.p[i]);
+      }
+      k3_convert_and_store<NRES>(P, w, rb, g, k, tau, y);
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < NRES; ++i)
+#pragma unroll
+        for (int s = 0; s < KS3; ++s) cur[i][s] = nxt[i][s];
+    }
+  }
+}
 
 }  // namespace rnswino

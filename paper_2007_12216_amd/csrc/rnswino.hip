@@ -137,8 +137,42 @@ void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t 
   }
 }
 
+// streaming variant: 8-bit moduli, table of all residues at most 64 KiB, n * KS3 <= 8 (O operand in registers twice)
+template <int NRES, int KS3>
+void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+  const long long blocks = ((long long)d.K * (d.Tp / 16) + 3) / 4;
+  const dim3 grid((unsigned)(blocks < K3_STREAM_BLOCKS ? blocks : K3_STREAM_BLOCKS));
+  const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
+  if (tm.start || tm.stop)
+    hipExtLaunchKernelGGL((k3_inverse_crt_stream<NRES, KS3>), grid, dim3(256), lds, st, tm.start, tm.stop, 0, P, O, y);
+  else
+    hipLaunchKernelGGL((k3_inverse_crt_stream<NRES, KS3>), grid, dim3(256), lds, st, P, O, y);
+}
+
+inline bool k3_stream_applies(const Dims &d) {
+  return !d.wide && d.n * d.KS3 <= 8 && d.n <= 4 && d.KS3 <= 2 && (size_t)d.n * d.RB3 * d.KS3 * 1024 <= 65536 &&
+         (long long)d.K * (d.Tp / 16) >= 4LL * K3_STREAM_BLOCKS;
+}
+
+void launch_k3_stream(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+  switch (d.n * 10 + d.KS3) {
+    case 11: launch_k3_stream_one<1, 1>(d, P, O, y, st, tm); break;
+    case 12: launch_k3_stream_one<1, 2>(d, P, O, y, st, tm); break;
+    case 21: launch_k3_stream_one<2, 1>(d, P, O, y, st, tm); break;
+    case 22: launch_k3_stream_one<2, 2>(d, P, O, y, st, tm); break;
+    case 31: launch_k3_stream_one<3, 1>(d, P, O, y, st, tm); break;
+    case 32: launch_k3_stream_one<3, 2>(d, P, O, y, st, tm); break;
+    case 41: launch_k3_stream_one<4, 1>(d, P, O, y, st, tm); break;
+    default: launch_k3_stream_one<4, 2>(d, P, O, y, st, tm); break;
+  }
+}
+
 template <bool WIDE>
 void launch_k3(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+  if (!WIDE && k3_stream_applies(d)) {   // many units: table in LDS, waves stream over the units
+    launch_k3_stream(d, P, O, y, st, tm);
+    return;
+  }
   switch (d.n) {
     case 1: launch_k3_nres<1, WIDE>(d, P, O, y, st, tm); break;
     case 2: launch_k3_nres<2, WIDE>(d, P, O, y, st, tm); break;
