@@ -14,8 +14,8 @@
 // sum_i w_i/p_i = y/P + integer with |y/P| <= 1/2 - 1/(2P), and the error of the sum is below 1e-14 while
 // 1/(2P) > 1e-10 for every moduli set whose product can matter for a 32-bit result.
 //
-// Block = one (k, block of 16 tiles); its waves take the 16-output row blocks rb = wave, wave+4, ...; every wave
-// loads the O operand itself (the copies hit in L1).  No LDS.  Grid: K * Tp/16 blocks of 256 threads.
+// Block = one (k, block of 16 tiles) and four 16-output row blocks rb = 4*blockIdx.y + wave; every wave loads the
+// O operand itself (the copies hit in L1).  No LDS.  Grid: x = K * Tp/16, y = ceil(RB3/4); 256 threads.
 // 16-bit moduli: table and O are two byte planes each; three accumulators as in the GEMM.
 #pragma once
 #include "kernels_common.hpp"
@@ -96,7 +96,8 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
   constexpr int PL = WIDE ? 2 : 1;
   constexpr int NACC = WIDE ? 3 : 1;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
-  if (wave >= P.RB3) return;
+  const int rb = blockIdx.y * 4 + wave;            // this wave's block of 16 outputs
+  if (rb >= P.RB3) return;
   const int ntb = P.Tp >> 4;
   // Workgroups go to the 8 XCDs round-robin by id.  Two neighbouring tile blocks of one k share a 128-byte line of
   // O, so the tile blocks of a k are given ids that differ by multiples of 8: one L2 fetches each line once.
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
         }
       }
 
-  for (int rb = wave; rb < P.RB3; rb += 4) {
+  {
     uint32_t w[NRES][4];
 #pragma unroll
     for (int i = 0; i < NRES; ++i) {
