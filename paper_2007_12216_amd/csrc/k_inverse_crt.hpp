@@ -14,8 +14,9 @@
 // sum_i w_i/p_i = y/P + integer with |y/P| <= 1/2 - 1/(2P), and the error of the sum is below 1e-14 while
 // 1/(2P) > 1e-10 for every moduli set whose product can matter for a 32-bit result.
 //
-// Block = one (k, block of 16 tiles) and four 16-output row blocks rb = 4*blockIdx.y + wave; every wave loads the
-// O operand itself (the copies hit in L1).  No LDS.  Grid: x = K * Tp/16, y = ceil(RB3/4); 256 threads.
+// Block = one unit of 16 consecutive (k, tile) pairs and four 16-output row blocks rb = 4*blockIdx.y + wave; every
+// wave loads the O operand itself (the copies hit in L1).  No LDS.
+// Grid: x = ceil(K*T/16) rounded up to a multiple of 8, y = ceil(RB3/4); 256 threads.
 // 16-bit moduli: table and O are two byte planes each; three accumulators as in the GEMM.
 #pragma once
 #include "kernels_common.hpp"
@@ -98,21 +99,16 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
   const int rb = blockIdx.y * 4 + wave;            // this wave's block of 16 outputs
   if (rb >= P.RB3) return;
-  const int ntb = P.Tp >> 4;
-  // Workgroups go to the 8 XCDs round-robin by id.  Two neighbouring tile blocks of one k share a 128-byte line of
-  // O, so the tile blocks of a k are given ids that differ by multiples of 8: one L2 fetches each line once.
-  int k, tb;
-  {
-    const int id = blockIdx.x, full = (P.K >> 3) * 8 * ntb;   // ids covering the k's below the last multiple of 8
-    if (id < full) {
-      tb = (id >> 3) % ntb;
-      k = (id & 7) + 8 * (id / (8 * ntb));
-    } else {
-      k = (P.K >> 3) * 8 + (id - full) / ntb;
-      tb = (id - full) % ntb;
-    }
-  }
-  const int tau = tb * 16 + (lane & 15);
+  // A unit is 16 consecutive (k, tile) pairs of the flattened K x T index space (no padding tiles: a unit may span
+  // several k's).  Workgroups go to the 8 XCDs round-robin by id; neighbouring units share 128-byte lines of O, so
+  // each XCD gets one contiguous chunk of the units (grid.x is a multiple of 8).
+  const long long npairs = (long long)P.K * P.T;
+  const int unit = xcd_chunked(blockIdx.x, gridDim.x, (int)((npairs + 15) >> 4));
+  if (unit < 0) return;
+  const long long pair = (long long)unit * 16 + (lane & 15);
+  const bool pair_ok = pair < npairs;
+  const int k = pair_ok ? (int)(pair / P.T) : 0;
+  const int tau = pair_ok ? (int)(pair - (long long)k * P.T) : P.T;   // tau = T marks a padding lane
 
   v4i of[NRES][KS3][PL];
 #pragma unroll
@@ -122,7 +118,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int q = 16 * s + 4 * g + e;
-        const bool ok = q < P.Q && tau < P.T;
+        const bool ok = q < P.Q && pair_ok;
         const uint32_t *src = O + ((((size_t)k * P.n + i) * P.Q + q) * P.Tp + tau) * PL;
         if (WIDE) {
           v2i two = (v2i){0, 0};

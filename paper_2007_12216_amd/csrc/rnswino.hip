@@ -128,7 +128,8 @@ void launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V
 // ---- K3 ----
 template <int NRES, bool WIDE>
 void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
-  const dim3 grid((unsigned)(d.K * (d.Tp / 16)), (unsigned)((d.RB3 + 3) / 4));
+  const long long units = ((long long)d.K * d.T + 15) / 16;
+  const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)((d.RB3 + 3) / 4));   // x multiple of 8: see xcd_chunked()
   switch (d.KS3) {
     case 1: launch(k3_inverse_crt<NRES, 1, WIDE>, grid, st, tm, P, O, y); break;
     case 2: launch(k3_inverse_crt<NRES, 2, WIDE>, grid, st, tm, P, O, y); break;
