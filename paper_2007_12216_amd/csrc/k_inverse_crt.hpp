@@ -3,7 +3,7 @@
 // Y_i = A^T_p O_i A_p after the reduction over C (paper section 6, eq. "direct_sum_2"), then the residues
 // (Y_0..Y_{n-1}) are converted to the integer result (section 3).  A^T O A = (A^T kron A^T) vec(O): per residue
 // an (m*m) x (t*t) matrix applied to the t*t transform points of a (channel k, tile) pair.  MFMA roles: A operand =
-// the Kronecker table (rows = 16 outputs), B operand = O (columns = 16 consecutive tiles of one channel k),
+// the Kronecker table (rows = 16 outputs), B operand = O (columns = 16 consecutive (k, tile) pairs),
 // contraction index = transform point; a lane's 16 operand bytes are four O words (groups q = 16s + 4g + e).
 //
 // Conversion: the table rows are pre-multiplied by (P/p_i)^-1 mod p_i (P = prod p_i), so the reduced accumulator
