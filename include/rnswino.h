@@ -38,8 +38,8 @@ extern "C" {
 enum {
   RNSWINO_OK = 0,
   RNSWINO_E_INVALID = -1,              /* null pointer, non-positive size, t > 16, m < 1, output empty      */
-  RNSWINO_E_UNSUPPORTED = -2,          /* stride != 1, even modulus, modulus < 3 or > 65521, 8/16-bit mix,
-                                          K-sum too long for the 32-bit accumulator of the residue GEMM      */
+  RNSWINO_E_UNSUPPORTED = -2,          /* stride != 1, r > 7, even modulus, modulus < 3, in 254..256 or > 65521,
+                                          8/16-bit mix, 2^14 r^2 C beyond int32, fused glue on other tile sizes */
   RNSWINO_E_NOT_COPRIME = -3,          /* two moduli share a factor (section 3: pairwise coprime)           */
   RNSWINO_E_POINT_NOT_INVERTIBLE = -4, /* a modulus shares a factor with a difference of two interpolation
                                           points, so a denominator of V^-1 has no inverse (section 5)       */
@@ -62,7 +62,7 @@ typedef struct rnswino_plan_s rnswino_plan_t;   /* opaque, owned by the library 
 
 typedef struct {
   int32_t  N, C, K, H, W;   /* activations x: int8 [N][C][H][W]                                              */
-  int32_t  r;               /* filter r x r; weights w: int8 [K][C][r][r]                                    */
+  int32_t  r;               /* filter r x r, 1 <= r <= 7; weights w: int8 [K][C][r][r]                       */
   int32_t  m;               /* output tile m x m; transform tile t = m + r - 1, 2 <= t <= 16                */
   int32_t  pad;             /* zeros added on each side of H and W (>= 0)                                   */
   int32_t  stride;          /* must be 1 (0 is read as 1)                                                    */

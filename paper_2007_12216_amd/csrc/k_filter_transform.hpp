@@ -16,11 +16,11 @@ __global__ void k0_filter_transform(KParams P, const int8_t *__restrict__ w, int
   const int i = (int)(idx / P.Kp);
   const int p = P.p[i], t = P.t, r = P.r;
   const int32_t *G = P.G + (size_t)i * t * r;
-  int g[25];
+  int g[49];                       // r <= 7 (checked by the plan)
   const bool live = (k < P.K) && (c < P.C);
   for (int e = 0; e < r * r; ++e) g[e] = live ? (int)w[((size_t)k * P.C + c) * r * r + e] : 0;
   for (int xi = 0; xi < t; ++xi) {
-    long long row[5];
+    long long row[7];
     for (int b = 0; b < r; ++b) {
       long long s = 0;
       for (int a = 0; a < r; ++a) s += (long long)G[xi * r + a] * g[a * r + b];

@@ -137,6 +137,7 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   if (d.n_moduli < 1 || d.n_moduli > 8) return RNSWINO_E_INVALID;
   const int t = d.m + d.r - 1;
   if (t < 2 || t > 16) return RNSWINO_E_INVALID;
+  if (d.r > 7) return RNSWINO_E_UNSUPPORTED;   // the filter-transform kernel keeps an r x r filter in registers
   if (d.stride != 0 && d.stride != 1) return RNSWINO_E_UNSUPPORTED;
   const long Ho = (long)d.H + 2L * d.pad - d.r + 1, Wo = (long)d.W + 2L * d.pad - d.r + 1;
   if (Ho <= 0 || Wo <= 0) return RNSWINO_E_INVALID;

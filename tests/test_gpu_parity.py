@@ -219,3 +219,43 @@ def test_fused_requant_refuses_unsupported_tiles():
     with pytest.raises(rn.RnsWinoError) as e:
         rn.rnswino_conv2d_requant(layer.plan, a, layer.U, a, 9, False, layer.workspace, 0)
     assert e.value.code == -2
+
+
+def _random_cases(count, seed):
+    """Seeded random layer shapes covering odd sizes, every filter size up to 7, 1..8 moduli of both widths."""
+    rng = np.random.default_rng(seed)
+    primes8 = [251, 241, 239, 233, 229, 227, 223, 211, 199, 197, 193, 191]
+    primes16 = [65521, 65519, 65497, 65479, 4001, 40009]
+    cases = []
+    while len(cases) < count:
+        r = int(rng.choice([1, 2, 3, 3, 3, 5, 5, 7]))
+        m = int(rng.integers(1, 17 - r + 1))
+        if m + r - 1 < 2:
+            continue
+        wide = bool(rng.integers(0, 4) == 0)
+        n = int(rng.integers(2, 4)) if wide else int(rng.integers(3, 9))
+        moduli = tuple((primes16 if wide else primes8)[:n])
+        N = int(rng.integers(1, 3))
+        C = int(rng.choice([1, 3, 17, 64, 65, 130]))
+        K = int(rng.choice([1, 5, 16, 33, 70]))
+        H, W = int(rng.integers(max(1, r - 2), 30)), int(rng.integers(max(1, r - 2), 30))
+        pad = int(rng.integers(0, r))
+        if H + 2 * pad - r + 1 <= 0 or W + 2 * pad - r + 1 <= 0:
+            continue
+        P = 1
+        for p in moduli:
+            P *= p
+        if (1 << 14) * r * r * C > (P - 1) // 2:
+            continue
+        cases.append((N, C, K, H, W, r, m, pad, moduli))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(40, 2024))
+def test_random_shapes_are_bit_exact(case):
+    N, C, K, H, W, r, m, pad, moduli = case
+    print("random case", case, flush=True)
+    x = si.int8_tensor(501, (N, C, H, W))
+    w = si.int8_tensor(502, (K, C, r, r))
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    assert np.array_equal(y, direct_conv2d(x, w, pad))

@@ -83,6 +83,7 @@ def test_error_codes():
     assert _code(C=0) == -1 and _code(m=0) == -1 and _code(m=15) == -1          # t = 17 > 16
     assert _code(H=1, W=1, pad=0) == -1                                          # empty output
     assert _code(stride=2) == -2
+    assert _code(r=8, m=4, pad=3) == -2                                          # filters above 7x7
     assert _code(moduli=(250, 241)) == -2 and _code(moduli=(251, 65521)) == -2 and _code(moduli=(255, 241, 239)) == -2
     assert _code(moduli=(251, 241, 241)) == -3 and _code(moduli=(249, 243, 241)) == -3
     assert _code(moduli=()) == -1 and _code(moduli=(3, 5, 7, 11, 13, 17, 19, 23, 29)) == -1
