@@ -97,7 +97,7 @@ size_t rnswino_filter_bytes(const rnswino_plan_t *plan);
 size_t rnswino_workspace_bytes(const rnswino_plan_t *plan);
 
 /*
- * Offline filter transform (section 6: "can be pre-calculated"):
+ * Offline filter transform (section 6: it depends on the weights only, so it is computed ahead of time):
  *   U[i][xi,nu][k][c] = (G_p g^(c)(k) G_p^T)[xi,nu] mod m_i.
  * w_dev: int8 [K][C][r][r].  U_dev: rnswino_filter_bytes() bytes, 256-byte aligned, written in the library's
  * own tiled layout; it stays valid for any plan with the same C, K, r, m and moduli.

@@ -16,7 +16,7 @@ Readings where the paper leaves a choice (each also listed in the design notes):
     F(2,3), F(4,3) and F(10,3) examples, continued for other sizes;
   * the point at infinity contributes the row (0,...,0,1) to the Vandermonde
     matrix (it evaluates the leading coefficient);
-  * "the fractions in B^T are arranged into matrix G": row j of V^{-T} is
+  * the fractions of B^T are moved into G (section 4 says so without giving the rule): row j of V^{-T} is
     multiplied by |prod_{l != j}(S_j - S_l)| and row j of G divided by it,
     which reproduces every matrix printed in the paper;
   * residues are kept in the symmetric range [-(p-1)/2, (p-1)/2] (the remark

@@ -1,5 +1,5 @@
 // K0: offline filter transform  U[i][xi,nu][k][c] = (G_p g G_p^T)[xi,nu] mod p_i   (paper section 6: the
-// transform of the filters "can be pre-calculated").  One thread per (residue, k, c) of the padded K x C grid;
+// filter transform depends on the weights only and is computed ahead of time).  One thread per (residue, k, c) of the padded K x C grid;
 // padding rows and channels are written as zeros, which is what lets the GEMM ignore them.
 #pragma once
 #include "kernels_common.hpp"
