@@ -7,7 +7,7 @@
  * result of the quantised layer (abstract; conclusions), so the reference is
  * the definition itself:
  *   - orientation: correlation, y_k = sum_j d_{k+j} g_j, no filter flip
- *     (section 3.1, "Convolution in RNS");
+ *     (section 3.1, the subsection on convolution in the RNS);
  *   - layer shape: K filters of r x r x C applied to a batch of C-channel
  *     planes, summed over the depth C (section 6, first paragraph);
  *   - stride 1 (strided layers are excluded in the paper's Table 5 footnote);

@@ -9,8 +9,7 @@ Generator: the splitmix64 stream (Steele, Lea, Flood, "Fast splittable
 pseudorandom number generators", OOPSLA 2014).  Element k of a tensor filled
 in memory order is the top byte of the k-th 64-bit output, reinterpreted as a
 signed byte, i.e. i.i.d. uniform on [-128, 127] -- the value range the paper
-states for quantised weights and activations (section 6, "signed integers,
-e.g. from -128 to 127").
+states for quantised weights and activations (section 6: signed 8-bit integers).
 """
 from __future__ import annotations
 
