@@ -246,6 +246,27 @@ def main():
         cpu = {"value": round(ops / best / 1e12, 6), "unit": "TOPS", "cores": num_threads(), "kind": "oracle",
                "sample": f"whole layer ({ops / 1e9:.3f} GOP), best of {reps} runs, {best * 1e3:.1f} ms"}
 
+    # ---- context: the vendor library's int8 GEMM on the im2col shape of this layer (K x C r^2 times C r^2 x N Ho Wo) ------
+    # This is the GEMM of the Im2col + INT8 GEMM baseline the paper compares against (its section 8), without the im2col
+    # step itself; PyTorch routes torch._int_mm to hipBLASLt.  Context only: it is not part of this library.
+    lib_gemm = None
+    try:
+        Mg, Kg, Ng = cfg["K"], cfg["C"] * cfg["r"] ** 2, cfg["N"] * plan.Ho * plan.Wo
+        Ng8 = -(-Ng // 8) * 8
+        ga = torch.randint(-128, 127, (Mg, Kg), dtype=torch.int8, device=dev)
+        gb = torch.randint(-128, 127, (Kg, Ng8), dtype=torch.int8, device=dev)
+        for _ in range(10):
+            torch._int_mm(ga, gb)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(100):
+            torch._int_mm(ga, gb)
+        torch.cuda.synchronize()
+        lib_gemm = {"us": round((time.perf_counter() - t0) / 100 * 1e6, 2), "shape": [Mg, Kg, Ng8],
+                    "what": "torch._int_mm (hipBLASLt) on the im2col GEMM of this layer, im2col itself not included"}
+    except Exception as exc:  # private API: absent or unsupported shapes are not an error of this benchmark
+        lib_gemm = {"us": None, "what": f"torch._int_mm unavailable: {type(exc).__name__}"}
+
     out = {
         "metric": "effective INT8 TOPS per conv layer (direct-conv ops/s)",
         "value": round(ops / sec_cold / 1e12, 3),
@@ -260,7 +281,7 @@ def main():
                    "direct_conv_GOP": round(ops / 1e9, 4), "cache": f"cold (rotation of {n_sets} operand sets, "
                    f"{n_sets * set_bytes >> 20} MiB)",
                    "warm_value_TOPS": round(ops / sec_warm / 1e12, 3), "warm_ms_per_step": round(sec_warm * 1e3, 5),
-                   "bit_exact_vs_oracle": bit_exact},
+                   "bit_exact_vs_oracle": bit_exact, "library_int8_gemm_context": lib_gemm},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
