@@ -29,7 +29,8 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   constexpr int ROWS = 4 * KS1;
   constexpr int PL = WIDE ? 2 : 1;
   __shared__ __attribute__((aligned(16))) uint8_t xs[64 * ROWS * 16];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: table addresses stay scalar
+  const int lane = threadIdx.x & 63, g = lane >> 4;
   const int ncb = P.Cp >> 6;
   const int i0 = gridDim.y == 1 ? 0 : blockIdx.y, i1 = gridDim.y == 1 ? P.n : i0 + 1;   // residues of this block
   const int unit = xcd_chunked(blockIdx.x, gridDim.x, P.T * ncb);   // neighbouring tiles (shared image lines) on one XCD
@@ -50,12 +51,14 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
       cmask[d] = mk;
     }
     const long long total = (long long)P.N * P.C * P.H * P.W;
+    // byte index of (channel cb*64, row y0, column x0) of this image: block-uniform; a task adds 32 bits to it
+    const long long patch0 = (((long long)img * P.C + cb * 64) * P.H + y0) * P.W + x0;
     for (int task = threadIdx.x; task < 64 * ROWS; task += 256) {
       const int c = task / ROWS, a = task - c * ROWS;
       const int gc = cb * 64 + c, gy = y0 + a;
       v4i val = (v4i){0, 0, 0, 0};
       if (gc < P.C && a < P.t && gy >= 0 && gy < P.H) {
-        const long long b0 = (((long long)img * P.C + gc) * P.H + gy) * P.W + x0;
+        const long long b0 = patch0 + (c * P.H + a) * P.W;      // 64 * H * W stays far below 2^31
         if (b0 >= 0 && b0 + 16 <= total) {
           __builtin_memcpy(&val, x + b0, 16);          // one unaligned 16-byte load
         } else {                                       // first / last bytes of the tensor

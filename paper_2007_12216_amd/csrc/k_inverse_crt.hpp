@@ -24,12 +24,35 @@
 namespace rnswino {
 
 
+// Where the output tile of a (k, tile) pair starts in y (or in the int8 activation plane): computed once per pair,
+// the row blocks of the pair only add their own row and column to it.
+struct TilePos {
+  size_t origin;     // element index of output (oy0, ox0) of channel k of image img
+  int oy0, ox0;      // top-left output of the tile
+  bool ok;           // false for padding tiles and padding pairs
+};
+
+__device__ __forceinline__ TilePos tile_position(const KParams &P, int k, int tau) {
+  TilePos tp;
+  tp.ok = tau < P.T;
+  const int trow = tau / P.tw;
+  const int tx = tau - trow * P.tw;
+  const int img = trow / P.th;
+  const int ty = trow - img * P.th;
+  tp.oy0 = ty * P.m;
+  tp.ox0 = tx * P.m;
+  const size_t plane = (size_t)img * P.K + k;
+  if (P.epi == 2) tp.origin = (plane * (P.Ho >> 1) + (tp.oy0 >> 1)) * (P.Wo >> 1) + (tp.ox0 >> 1);
+  else tp.origin = (plane * P.Ho + tp.oy0) * P.Wo + tp.ox0;
+  return tp;
+}
+
 // CRT conversion of the four outputs of one lane (row block rb, lane group g) and their store: int32 y, or, for
 // chained layers, int8 clamp(y >> shift) with an optional 2x2 max-pool (the shift is monotone, so it commutes with
 // the max).  Must be called by all lanes of a wave (the pooled mode exchanges rows between lanes).
 template <int NRES>
 __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uint32_t (&w)[NRES][4], int rb, int g,
-                                                     int k, int tau, int32_t *__restrict__ y) {
+                                                     const TilePos &tp, int32_t *__restrict__ y) {
   int val[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -44,49 +67,43 @@ __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uin
     val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
   }
   const int m = P.m, mm = m * m;
-  const bool tile_ok = tau < P.T;
-  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
   const float inv_m = 1.0f / (float)m;
   const int o0 = 16 * rb + 4 * g;
   if (P.epi != 0) {
     // host guarantees m in {4, 8}, Wo % 4 == 0, even Ho and Wo when pooling
     const int u = (int)(((float)o0 + 0.5f) * inv_m);
     const int v = o0 - u * m;
-    const int oy = ty * m + u, ox = tx * m + v;
+    const bool inside = tp.ok && o0 < mm && tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo;
     if (P.epi == 1) {
       uint32_t packed = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) packed |= ((uint32_t)min(127, max(-128, val[j] >> P.shift)) & 0xFFu) << (8 * j);
-      int8_t *aplane = P.act + ((size_t)img * P.K + k) * P.Ho * P.Wo;
-      if (tile_ok && o0 < mm && oy < P.Ho && ox < P.Wo) *(uint32_t *)(aplane + (size_t)oy * P.Wo + ox) = packed;
+      if (inside) *(uint32_t *)(P.act + tp.origin + (uint32_t)(u * P.Wo + v)) = packed;
     } else {
       // rows u and u+1 (u even) of an output tile sit in lanes l and l ^ 4m (m = 8: 32 apart, m = 4: 16 apart)
       const int h0 = max(val[0], val[1]), h1 = max(val[2], val[3]);
       const int delta = 4 * m;
       const int o0p = __shfl_xor(h0, delta), o1p = __shfl_xor(h1, delta);
       const int p0 = min(127, max(-128, max(h0, o0p) >> P.shift)), p1 = min(127, max(-128, max(h1, o1p) >> P.shift));
-      const int Hq = P.Ho >> 1, Wq = P.Wo >> 1;
-      int8_t *aplane = P.act + ((size_t)img * P.K + k) * Hq * Wq;
-      if (tile_ok && o0 < mm && (u & 1) == 0 && oy < P.Ho && ox < P.Wo)
-        *(uint16_t *)(aplane + (size_t)(oy >> 1) * Wq + (ox >> 1)) = (uint16_t)(((uint32_t)p0 & 0xFFu) | (((uint32_t)p1 & 0xFFu) << 8));
+      if (inside && (u & 1) == 0)
+        *(uint16_t *)(P.act + tp.origin + (uint32_t)((u >> 1) * (P.Wo >> 1) + (v >> 1))) =
+            (uint16_t)(((uint32_t)p0 & 0xFFu) | (((uint32_t)p1 & 0xFFu) << 8));
     }
     return;
   }
-  if (!tile_ok || o0 >= mm) return;
-  int32_t *yplane = y + ((size_t)img * P.K + k) * P.Ho * P.Wo;
+  if (!tp.ok || o0 >= mm) return;
+  int32_t *ytile = y + tp.origin;
   if (((m & 3) == 0) && ((P.Wo & 3) == 0)) {   // four consecutive outputs stay in one row, 16-byte aligned
     const int u = (int)(((float)o0 + 0.5f) * inv_m);
     const int v = o0 - u * m;
-    const int oy = ty * m + u, ox = tx * m + v;
-    if (oy < P.Ho && ox < P.Wo) *(v4i *)(yplane + (size_t)oy * P.Wo + ox) = (v4i){val[0], val[1], val[2], val[3]};
+    if (tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo) *(v4i *)(ytile + (uint32_t)(u * P.Wo + v)) = (v4i){val[0], val[1], val[2], val[3]};
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int o = o0 + j;
       const int u = (int)(((float)o + 0.5f) * inv_m);
       const int v = o - u * m;
-      const int oy = ty * m + u, ox = tx * m + v;
-      if (o < mm && oy < P.Ho && ox < P.Wo) yplane[(size_t)oy * P.Wo + ox] = val[j];
+      if (o < mm && tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo) ytile[(uint32_t)(u * P.Wo + v)] = val[j];
     }
   }
 }
@@ -96,39 +113,48 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
                                                        int32_t *__restrict__ y) {
   constexpr int PL = WIDE ? 2 : 1;
   constexpr int NACC = WIDE ? 3 : 1;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: row block and table addresses stay scalar
+  const int lane = threadIdx.x & 63, g = lane >> 4;
   const int rb = blockIdx.y * 4 + wave;            // this wave's block of 16 outputs
   if (rb >= P.RB3) return;
   // A unit is 16 consecutive (k, tile) pairs of the flattened K x T index space (no padding tiles: a unit may span
   // several k's).  Workgroups go to the 8 XCDs round-robin by id; neighbouring units share 128-byte lines of O, so
   // each XCD gets one contiguous chunk of the units (grid.x is a multiple of 8).
-  const long long npairs = (long long)P.K * P.T;
-  const int unit = xcd_chunked(blockIdx.x, gridDim.x, (int)((npairs + 15) >> 4));
+  const int npairs = P.K * P.T;                    // below 2^31 (checked when the plan is made)
+  const int unit = xcd_chunked(blockIdx.x, gridDim.x, (npairs + 15) >> 4);
   if (unit < 0) return;
-  const long long pair = (long long)unit * 16 + (lane & 15);
+  const int pair = unit * 16 + (lane & 15);
   const bool pair_ok = pair < npairs;
-  const int k = pair_ok ? (int)(pair / P.T) : 0;
-  const int tau = pair_ok ? (int)(pair - (long long)k * P.T) : P.T;   // tau = T marks a padding lane
+  const int k = pair_ok ? pair / P.T : 0;
+  const int tau = pair_ok ? pair - k * P.T : P.T;   // tau = T marks a padding lane (its loads stay inside row k = 0)
 
+  // O is [Kp][n][Q][Tp] words (x PL planes) and smaller than 4 GiB: the address of a word is a wave-uniform row
+  // (residue, point group 16s + e) plus a 32-bit lane offset (k, lane group 4g, tile).  Point groups >= Q of the
+  // last contraction step are clamped to Q - 1: the table is zero there, so whatever is read does not count.
+  const uint32_t rowstride = (uint32_t)P.Tp * PL;
+  const uint32_t lane_off = (uint32_t)(k * P.n * P.Q) * rowstride + (uint32_t)tau * PL;
+  uint32_t voff[KS3][4];
+#pragma unroll
+  for (int s = 0; s < KS3; ++s)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) voff[s][e] = lane_off + (uint32_t)min(16 * s + 4 * g + e, P.Q - 1) * rowstride;
   v4i of[NRES][KS3][PL];
 #pragma unroll
-  for (int i = 0; i < NRES; ++i)
+  for (int i = 0; i < NRES; ++i) {       // residue by residue, the order in which the products below consume them
+    const uint32_t *row = O + (size_t)(i * P.Q) * rowstride;
 #pragma unroll
     for (int s = 0; s < KS3; ++s)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int q = 16 * s + 4 * g + e;
-        const bool ok = q < P.Q && pair_ok;
-        const uint32_t *src = O + ((((size_t)k * P.n + i) * P.Q + q) * P.Tp + tau) * PL;
         if (WIDE) {
-          v2i two = (v2i){0, 0};
-          if (ok) two = *(const v2i *)src;
+          const v2i two = *(const v2i *)(row + voff[s][e]);
           of[i][s][0][e] = two[0];
           of[i][s][PL - 1][e] = two[1];
         } else {
-          of[i][s][0][e] = ok ? (int)*src : 0;
+          of[i][s][0][e] = (int)row[voff[s][e]];
         }
       }
+  }
 
   {
     uint32_t w[NRES][4];
@@ -164,11 +190,9 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
         }
       }
     }
-    k3_convert_and_store<NRES>(P, w, rb, g, k, tau, y);
+    k3_convert_and_store<NRES>(P, w, rb, g, tile_position(P, k, tau), y);
   }
 }
-
-
 
 // Streaming variant for layers with many tiles (8-bit moduli, table of all residues <= 64 KiB): the table is staged
 // once per block in LDS, and every wave walks over units = (k, block of 16 tiles) with a grid stride, loading the O
@@ -181,29 +205,38 @@ template <int NRES, int KS3>
 __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const uint32_t *__restrict__ O,
                                                               int32_t *__restrict__ y) {
   extern __shared__ __attribute__((aligned(16))) uint8_t ka_lds[];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: unit arithmetic stays scalar
+  const int lane = threadIdx.x & 63, g = lane >> 4;
   const int ntb = P.Tp >> 4;
-  const long long nunits = (long long)P.K * ntb;
-  const long long nwaves = (long long)gridDim.x * 4;
+  const int nunits = P.K * ntb;                    // below 2^31 (checked when the plan is made)
+  const int nwaves = gridDim.x * 4;
   {
     const int bytes = NRES * P.RB3 * KS3 * 1024;
     for (int off = threadIdx.x * 16; off < bytes; off += 256 * 16) *(v4i *)(ka_lds + off) = *(const v4i *)(P.KA + off);
   }
   __syncthreads();
-  long long unit = (long long)blockIdx.x * 4 + wave;
+  int unit = blockIdx.x * 4 + wave;
   if (unit >= nunits) return;
 
-  auto load_o = [&](long long u, v4i (&of)[NRES][KS3]) {
-    const int k = (int)(u / ntb), tau = (int)(u % ntb) * 16 + (lane & 15);
+  // lane part of an O address, the same for every unit: point group (clamped to Q - 1 where the table is zero)
+  // and tile within the block of 16; the unit contributes a wave-uniform base
+  uint32_t voff[KS3][4];
 #pragma unroll
-    for (int i = 0; i < NRES; ++i)
+  for (int s = 0; s < KS3; ++s)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) voff[s][e] = (uint32_t)min(16 * s + 4 * g + e, P.Q - 1) * (uint32_t)P.Tp + (lane & 15);
+
+  auto load_o = [&](int u, v4i (&of)[NRES][KS3]) {
+    const int k = u / ntb, tb = u - k * ntb;
+    const uint32_t *base = O + (size_t)k * P.n * P.Q * P.Tp + tb * 16;
+#pragma unroll
+    for (int i = 0; i < NRES; ++i) {
+      const uint32_t *row = base + (size_t)(i * P.Q) * P.Tp;
 #pragma unroll
       for (int s = 0; s < KS3; ++s)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int q = 16 * s + 4 * g + e;
-          of[i][s][e] = (q < P.Q && tau < P.T) ? (int)O[((((size_t)k * P.n + i) * P.Q + q) * P.Tp + tau)] : 0;
-        }
+        for (int e = 0; e < 4; ++e) of[i][s][e] = (int)row[voff[s][e]];
+    }
   };
 
   v4i cur[NRES][KS3], nxt[NRES][KS3];
@@ -211,7 +244,8 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
   for (; unit < nunits; unit += nwaves) {
     const bool more = unit + nwaves < nunits;
     if (more) load_o(unit + nwaves, nxt);
-    const int k = (int)(unit / ntb), tau = (int)(unit % ntb) * 16 + (lane & 15);
+    const int k = unit / ntb, tau = (unit - k * ntb) * 16 + (lane & 15);
+    const TilePos tp = tile_position(P, k, tau);
     for (int rb = 0; rb < P.RB3; ++rb) {
       uint32_t w[NRES][4];
 #pragma unroll
@@ -226,7 +260,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
 #pragma unroll
         for (int j = 0; j < 4; ++j) w[i][j] = (uint32_t)(mod_near(acc[j], P.inv_p[i], P.p[i]) + P.p[i]);
       }
-      k3_convert_and_store<NRES>(P, w, rb, g, k, tau, y);
+      k3_convert_and_store<NRES>(P, w, rb, g, tp, y);
     }
     if (more) {
 #pragma unroll

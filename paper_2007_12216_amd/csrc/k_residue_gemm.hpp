@@ -27,7 +27,8 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
   constexpr int COLS = 16 * NTB;
   constexpr int ROWS = 16 * RM;          // k rows per wave and per block
   __shared__ uint32_t tile[ROWS * COLS * PL];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: slab addresses stay scalar
+  const int lane = threadIdx.x & 63;
   if (blockIdx.x >= P.n * P.Q) return;             // grid.x is padded to a multiple of 8 (one XCD per x residue class)
   const int i = blockIdx.x / P.Q, q = blockIdx.x % P.Q;
   const int pt = 4 * q + wave;
@@ -118,15 +119,19 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
         }
       }
   __syncthreads();
-  uint32_t *Ob = O + ((size_t)i * P.Q + q) * P.Tp * PL;      // + k * (n*Q*Tp*PL): O is [Kp][n][Q][Tp][PL]
-  const size_t krow = (size_t)P.n * P.Q * P.Tp * PL;
-  constexpr int ROWW = COLS * PL;   // words per tile row
+  // O is [Kp][n][Q][Tp] words (x PL) and smaller than 4 GiB: 32-bit word offsets, advanced by whole rows
+  constexpr int ROWW = COLS * PL;         // words per tile row; divides 256
+  constexpr int RSTEP = 256 / ROWW;       // rows covered by one pass of the block
+  const uint32_t krow = (uint32_t)(P.n * P.Q * P.Tp) * PL;
+  const int r0 = threadIdx.x / ROWW, rem = threadIdx.x % ROWW;
+  const int tau = tb0 * 16 + rem / PL;
+  uint32_t off = (uint32_t)(kb0 * 16 + r0) * krow + (uint32_t)((i * P.Q + q) * P.Tp + tb0 * 16) * PL + rem;
+  const bool col_ok = tau < P.T;          // padding tiles are neither written nor read
 #pragma unroll
   for (int it = 0; it < (ROWS * ROWW) / 256; ++it) {
-    const int e = it * 256 + threadIdx.x;
-    const int row = e / ROWW, rem = e % ROWW;
-    const int k = kb0 * 16 + row, tau = tb0 * 16 + rem / PL;
-    if (k < P.Kp && tau < P.T) Ob[(size_t)k * krow + (size_t)(tb0 * 16) * PL + rem] = tile[e];   // padding tiles are neither written nor read
+    const int k = kb0 * 16 + it * RSTEP + r0;
+    if (k < P.Kp && col_ok) O[off] = tile[it * 256 + threadIdx.x];
+    off += RSTEP * krow;
   }
 }
 

@@ -54,9 +54,13 @@ __device__ __forceinline__ int mod_near(int x, float inv_p, int p) {
 }
 
 // Low byte of that residue: the constant term 2^22 * p of the mantissa trick is a multiple of 256 and drops out.
+// (Written as the full-rate 24-bit multiply-add itself: since only the low byte is kept, the compiler would
+// otherwise swap it for a quarter-rate 64-bit multiply-add.)
 __device__ __forceinline__ uint32_t mod_lowbyte(int x, float inv_p, int neg_p) {
   const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
-  return (uint32_t)(__mul24(__float_as_int(f), neg_p) + x);
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(__float_as_int(f)), "v"(neg_p), "v"(x));
+  return (uint32_t)r;
 }
 
 // byte 0 of a, b, c, d -> one word

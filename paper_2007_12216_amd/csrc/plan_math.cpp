@@ -141,6 +141,7 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   if (d.stride != 0 && d.stride != 1) return RNSWINO_E_UNSUPPORTED;
   const long Ho = (long)d.H + 2L * d.pad - d.r + 1, Wo = (long)d.W + 2L * d.pad - d.r + 1;
   if (Ho <= 0 || Wo <= 0) return RNSWINO_E_INVALID;
+  if ((long long)d.H * d.W > (1LL << 24)) return RNSWINO_E_UNSUPPORTED;   // kernels offset 64 image planes in 32 bits
   int n8 = 0, n16 = 0;
   for (int i = 0; i < d.n_moduli; ++i) {
     const uint32_t p = d.moduli[i];
@@ -173,6 +174,10 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   o.KS1 = (t + 3) / 4;
   o.RB3 = (d.m * d.m + 15) / 16;
   o.KS3 = (o.P2 + 63) / 64;
+  // the kernels address the GEMM output O = [Kp][n][Q][Tp] words (two planes for 16-bit moduli) with 32-bit byte
+  // offsets and count (k, tile) pairs in 32 bits
+  const unsigned __int128 o_bytes = (unsigned __int128)o.Kp * o.n * o.Q * o.Tp * 4u * (o.wide ? 2u : 1u);
+  if (o_bytes >= ((unsigned __int128)1 << 32) || (long long)o.Kp * o.Tp >= (1LL << 31)) return RNSWINO_E_UNSUPPORTED;
   return RNSWINO_OK;
 }
 

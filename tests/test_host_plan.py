@@ -87,6 +87,10 @@ def test_error_codes():
     assert _code(moduli=(250, 241)) == -2 and _code(moduli=(251, 65521)) == -2 and _code(moduli=(255, 241, 239)) == -2
     assert _code(moduli=(251, 241, 241)) == -3 and _code(moduli=(249, 243, 241)) == -3
     assert _code(moduli=()) == -1 and _code(moduli=(3, 5, 7, 11, 13, 17, 19, 23, 29)) == -1
+    # size limits of the kernels' 32-bit offsets: GEMM output of 4 GiB or more, image planes above 2^24 pixels
+    assert _code(N=64, K=64, H=224, W=224) == 0                                  # 0.96 GB of O
+    assert _code(N=512, K=64, H=224, W=224) == -2                                # 7.7 GB of O
+    assert _code(H=4096, W=4096) == 0 and _code(H=4096, W=4104) == -2
 
 
 def test_invertibility_rule_of_section_5():
