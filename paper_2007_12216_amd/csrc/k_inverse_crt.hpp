@@ -50,21 +50,43 @@ __device__ __forceinline__ TilePos tile_position(const KParams &P, int k, int ta
 // CRT conversion of the four outputs of one lane (row block rb, lane group g) and their store: int32 y, or, for
 // chained layers, int8 clamp(y >> shift) with an optional 2x2 max-pool (the shift is monotone, so it commutes with
 // the max).  Must be called by all lanes of a wave (the pooled mode exchanges rows between lanes).
+template <int NRES, bool CRT24, bool QUOT32>
+__device__ __forceinline__ void crt_convert(const KParams &P, const uint32_t (&w)[NRES][4], int (&val)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t sum = 0;
+    int kk;
+    if (QUOT32) {
+      // |y| <= 0.45 P: the sum is within 0.45 of an integer and binary32 (error below 1e-4) finds that integer
+      float fs = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NRES; ++i) {
+        sum += CRT24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
+        fs = __builtin_fmaf((float)w[i][j], P.inv_p[i], fs);
+      }
+      kk = (int)__builtin_rintf(fs);
+    } else {
+      double fs = 0.0;
+#pragma unroll
+      for (int i = 0; i < NRES; ++i) {
+        sum += CRT24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
+        fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
+      }
+      kk = __double2int_rn(fs);
+    }
+    val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+  }
+}
+
 template <int NRES>
 __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uint32_t (&w)[NRES][4], int rb, int g,
                                                      const TilePos &tp, int32_t *__restrict__ y) {
   int val[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    uint32_t sum = 0;
-    double fs = 0.0;
-#pragma unroll
-    for (int i = 0; i < NRES; ++i) {
-      sum += P.crt24 ? __umul24(P.crt_c[i], w[i][j]) : P.crt_c[i] * w[i][j];
-      fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
-    }
-    const int kk = __double2int_rn(fs);
-    val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+  if (P.crt24) {                      // uniform: one branch per call instead of one per multiply
+    if (P.quot32) crt_convert<NRES, true, true>(P, w, val);
+    else crt_convert<NRES, true, false>(P, w, val);
+  } else {
+    crt_convert<NRES, false, false>(P, w, val);
   }
   const int m = P.m, mm = m * m;
   const float inv_m = 1.0f / (float)m;
@@ -186,7 +208,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
           w[i][j] = (uint32_t)(mod_near64(tot, P.inv_pd[i], P.p[i]) + P.p[i]);
         } else {
           // |acc| <= t*t * 126 * 127 < 2^24
-          w[i][j] = (uint32_t)(mod_near(acc[0][j], P.inv_p[i], P.p[i]) + P.p[i]);
+          w[i][j] = mod_near_plus_p(acc[0][j], P.inv_p[i], -P.p[i], P.bias_p[i]);
         }
       }
     }
@@ -258,7 +280,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
         }
         // |acc| <= t*t * 126 * 127 < 2^24; residue shifted by +p so that it is non-negative
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[i][j] = (uint32_t)(mod_near(acc[j], P.inv_p[i], P.p[i]) + P.p[i]);
+        for (int j = 0; j < 4; ++j) w[i][j] = mod_near_plus_p(acc[j], P.inv_p[i], -P.p[i], P.bias_p[i]);
       }
       k3_convert_and_store<NRES>(P, w, rb, g, tp, y);
     }

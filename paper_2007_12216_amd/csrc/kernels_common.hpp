@@ -26,6 +26,8 @@ struct KParams {
   uint32_t crt_c[8];          // prod_{l != i} p_l mod 2^32
   uint32_t prod_mod32;        // prod p_i mod 2^32
   int crt24;                  // every prod_{l != i} p_l is below 2^24: 24-bit multiplies suffice
+  int quot32;                 // the layer's worst-case |y| is at most 0.45 prod p_i: binary32 finds the CRT quotient
+  int bias_p[8];              // p_i * 2^22 + p_i (8-bit moduli), see mod_near_plus_p()
   // fused re-quantisation in the inverse-transform kernel (chained layers): 0 = store int32 y,
   // 1 = store int8 clamp(y >> shift), 2 = the same after a 2x2 stride-2 max-pool
   int epi, shift;
@@ -60,6 +62,15 @@ __device__ __forceinline__ uint32_t mod_lowbyte(int x, float inv_p, int neg_p) {
   const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
   int r;
   asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(__float_as_int(f)), "v"(neg_p), "v"(x));
+  return (uint32_t)r;
+}
+
+// That residue plus p (so that it is positive), 8-bit p: the low 24 bits of the biased float are 2^22 + q, the
+// 24-bit multiply-add gives x - q p - 2^22 p + bias with bias = 2^22 p + p.  Four full-rate instructions.
+__device__ __forceinline__ uint32_t mod_near_plus_p(int x, float inv_p, int neg_p, int bias) {
+  const float f = __builtin_fmaf((float)x, inv_p, 12582912.0f);
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(__float_as_int(f)), "v"(neg_p), "v"(x + bias));
   return (uint32_t)r;
 }
 

@@ -41,6 +41,15 @@ KParams make_params(const rnswino_plan_t *pl) {
     P.inv_pd[i] = 1.0 / (double)pl->desc.moduli[i];
     P.crt_c[i] = pl->crt_c[i];
     if (!pl->crt_c_exact_small[i]) P.crt24 = 0;
+    P.bias_p[i] = d.wide ? 0 : (int)(pl->desc.moduli[i] * 4194304u + pl->desc.moduli[i]);
+  }
+  {
+    // binary32 is enough for the CRT quotient when 2 * (worst-case |y|) <= 0.9 * prod p_i
+    unsigned __int128 prod = 1;
+    const unsigned __int128 cap = ((unsigned __int128)1 << 100);
+    for (int i = 0; i < d.n; ++i) { prod *= pl->desc.moduli[i]; if (prod > cap) prod = cap; }
+    const unsigned __int128 worst = (unsigned __int128)16384u * (unsigned)d.r * (unsigned)d.r * (unsigned)d.C;
+    P.quot32 = (worst * 20 <= prod * 9) ? 1 : 0;
   }
   P.prod_mod32 = pl->prod_mod32;
   const char *base = (const char *)pl->d_tables;

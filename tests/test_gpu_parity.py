@@ -88,6 +88,22 @@ def test_extreme_values(xv, wv):
     assert abs(int(ref[0, 0, 5, 5])) == abs(xv * wv) * 9 * C
 
 
+@pytest.mark.parametrize("C,moduli,sign", [(49, (251, 241, 239), 1), (49, (251, 241, 239), -1),
+                                           (16, (251, 241, 239), 1), (512, (65521, 65519), -1)])
+def test_results_at_the_edge_of_the_dynamic_range(C, moduli, sign):
+    """All-extreme tensors drive |y| to 2^14 * 9 * C: with C = 49 and RNS(251,241,239) that is 7 225 344 of the
+    7 228 674 the set can hold (section 3), so the CRT quotient is decided within 2.3e-4 of a half; C = 16 is the
+    comfortable case (both precisions of the quotient estimate are exercised)."""
+    print("range edge", C, moduli, sign, flush=True)
+    N, K, H, W, r, m, pad = 1, 16, 16, 16, 3, 8, 1
+    x = np.full((N, C, H, W), -128, dtype=np.int8)
+    w = np.full((K, C, r, r), -128 if sign > 0 else 127, dtype=np.int8)
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    ref = direct_conv2d(x, w, pad)
+    assert np.array_equal(y, ref)
+    assert abs(int(ref[0, 0, 5, 5])) == 128 * (128 if sign > 0 else 127) * 9 * C
+
+
 def test_unchecked_range_returns_the_symmetric_residue():
     print("unchecked range", flush=True)
     N, C, K, H, W, r, m, pad, moduli = 1, 50, 16, 8, 8, 3, 8, 1, (251, 241, 239)
