@@ -15,6 +15,9 @@ def build_library(verbose: bool = False) -> str:
     """Compile every source with hipcc for gfx950 and link the shared library."""
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # matrix-core results straight into ordinary vector registers: no accumulator-register copies in the
+           # epilogues, and fewer registers per wave
+           "-mllvm", "-amdgpu-mfma-vgpr-form=1",
            "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
