@@ -15,7 +15,7 @@
 // give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
 // 16-bit moduli: the table has a high and a low byte plane, V = (256 * sum_h + sum_l) mod p, stored as two planes.
 // Grid: x = T * Cp/64 rounded up to a multiple of 8 (see xcd_chunked), y = n (one residue per block) or 1 (the block
-// walks over all residues with the same gathered patch); 256 threads; 64 * 4*KS1 * 16 bytes of LDS.
+// walks over all residues with the same gathered patch); 256 threads; 64 * (4*KS1 + 1) * 16 bytes of LDS.
 #pragma once
 #include "kernels_common.hpp"
 
@@ -28,7 +28,9 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
                                                            int8_t *__restrict__ V) {
   constexpr int ROWS = 4 * KS1;
   constexpr int PL = WIDE ? 2 : 1;
-  __shared__ __attribute__((aligned(16))) uint8_t xs[64 * ROWS * 16];
+  constexpr int CROW = (ROWS + 1) * 16;   // bytes per channel in LDS: one 16-byte pad, so that the 16 channels a
+                                          // fragment read touches fall into different banks
+  __shared__ __attribute__((aligned(16))) uint8_t xs[64 * CROW];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: table addresses stay scalar
   const int lane = threadIdx.x & 63, g = lane >> 4;
   const int ncb = P.Cp >> 6;
@@ -71,48 +73,46 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
         }
         val[0] &= cmask[0]; val[1] &= cmask[1]; val[2] &= cmask[2]; val[3] &= cmask[3];
       }
-      *(v4i *)(xs + task * 16) = val;
+      *(v4i *)(xs + c * CROW + a * 16) = val;
     }
   }
-  // table fragments of this wave's first column-block group: issued before the barrier so that their latency
-  // overlaps the gather
+  // This wave's work: steps (residue i, column-block group cg) with cg = wave, wave + 4, ...  The table fragments
+  // of step k+1 are requested before step k is multiplied; those of step 0 before the barrier, so that their
+  // latency overlaps the gather.
   const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
-  const int8_t *KBi = P.KB + (size_t)i0 * P.CB1 * KS1 * PL * 1024 + lane * 16;
-  v4i bf[K1_CPW][KS1][PL];
+  const int per_i = (ncg - wave + 3) >> 2;            // groups of this wave per residue
+  const int nsteps = (i1 - i0) * per_i;
+  auto load_table = [&](int step, v4i (&b)[K1_CPW][KS1][PL]) {
+    const int i = i0 + step / per_i, cg = wave + 4 * (step % per_i);
+    const int8_t *KBi = P.KB + (size_t)i * P.CB1 * KS1 * PL * 1024 + lane * 16;
 #pragma unroll
-  for (int cc = 0; cc < K1_CPW; ++cc)
+    for (int cc = 0; cc < K1_CPW; ++cc)
 #pragma unroll
-    for (int s = 0; s < KS1; ++s)
+      for (int s = 0; s < KS1; ++s)
 #pragma unroll
-      for (int pl = 0; pl < PL; ++pl) {
-        const int cbk = min(wave * K1_CPW + cc, P.CB1 - 1);
-        bf[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
-      }
+        for (int pl = 0; pl < PL; ++pl) {
+          const int cbk = min(cg * K1_CPW + cc, P.CB1 - 1);
+          b[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
+        }
+  };
+  v4i bf[K1_CPW][KS1][PL], bn[K1_CPW][KS1][PL];
+  if (nsteps > 0) load_table(0, bf);
   __syncthreads();
+  if (nsteps <= 0) return;
 
   v4i af[4][KS1];
 #pragma unroll
   for (int u = 0; u < 4; ++u)
 #pragma unroll
-    for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + ((16 * u + (lane & 15)) * ROWS + 4 * s + g) * 16);
+    for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + (16 * u + (lane & 15)) * CROW + (4 * s + g) * 16);
 
-  for (int i = i0; i < i1; ++i) {
-  KBi = P.KB + (size_t)i * P.CB1 * KS1 * PL * 1024 + lane * 16;
-  const int p = P.p[i];
-  const float inv = P.inv_p[i];
-  const double invd = P.inv_pd[i];
-  for (int cg = wave; cg < ncg; cg += 4) {
-    if (cg != wave || i != i0) {
-#pragma unroll
-      for (int cc = 0; cc < K1_CPW; ++cc)
-#pragma unroll
-        for (int s = 0; s < KS1; ++s)
-#pragma unroll
-          for (int pl = 0; pl < PL; ++pl) {
-            const int cbk = min(cg * K1_CPW + cc, P.CB1 - 1);
-            bf[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
-          }
-    }
+  for (int step = 0; step < nsteps; ++step) {
+    const bool more = step + 1 < nsteps;
+    if (more) load_table(step + 1, bn);
+    const int i = i0 + step / per_i, cg = wave + 4 * (step % per_i);
+    const int p = P.p[i];
+    const float inv = P.inv_p[i];
+    const double invd = P.inv_pd[i];
 #pragma unroll
     for (int cc = 0; cc < K1_CPW; ++cc) {
       const int cbk = cg * K1_CPW + cc;
@@ -162,8 +162,15 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
         if (pt < P.P2) *(v4i *)dst = out;
       }
     }
+    if (more) {
+#pragma unroll
+      for (int cc = 0; cc < K1_CPW; ++cc)
+#pragma unroll
+        for (int s = 0; s < KS1; ++s)
+#pragma unroll
+          for (int pl = 0; pl < PL; ++pl) bf[cc][s][pl] = bn[cc][s][pl];
+    }
   }
-  }  // residues
 }
 
 }  // namespace rnswino

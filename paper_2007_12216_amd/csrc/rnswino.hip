@@ -86,9 +86,10 @@ inline void launch(Kern kern, dim3 grid, hipStream_t st, Timing tm, Args... args
 template <bool WIDE>
 void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
   // x: multiple of 8 (see xcd_chunked()); y: one block per residue, or one block for all residues when there are
-  // enough units to fill the chip (the pixel gather is then done once instead of n times)
+  // enough units to fill the chip (the pixel gather is then done once instead of n times; measured on the VGG16
+  // stack, two blocks per CU are already enough for that to win)
   const long long units = (long long)d.T * (d.Cp / 64);
-  const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)(units >= 4096 ? 1 : d.n));
+  const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)(units >= 512 ? 1 : d.n));
   switch (d.KS1) {
     case 1: launch(k1_input_transform<1, WIDE>, grid, st, tm, P, x, V); break;
     case 2: launch(k1_input_transform<2, WIDE>, grid, st, tm, P, x, V); break;
