@@ -99,6 +99,9 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   if (nsteps > 0) load_table(0, bf);
   __syncthreads();
   if (nsteps <= 0) return;
+  // All loads issued so far are awaited here, explicitly: otherwise the compiler, merging this entry state with the
+  // loop's own, makes every step wait for the fragments it has just requested for the next one.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
 
   v4i af[4][KS1];
 #pragma unroll
@@ -106,9 +109,11 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
 #pragma unroll
     for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + (16 * u + (lane & 15)) * CROW + (4 * s + g) * 16);
 
-  for (int step = 0; step < nsteps; ++step) {
-    const bool more = step + 1 < nsteps;
-    if (more) load_table(step + 1, bn);
+  // One step with the fragments in `b`, while those of the following step travel into `bnext`.  The loop below
+  // alternates the two register sets instead of copying one into the other: a copy would have to wait for every
+  // memory operation issued before it, the step's own stores included.
+  auto do_step = [&](int step, v4i (&b)[K1_CPW][KS1][PL], v4i (&bnext)[K1_CPW][KS1][PL]) {
+    if (step + 1 < nsteps) load_table(step + 1, bnext);
     const int i = i0 + step / per_i, cg = wave + 4 * (step % per_i);
     const int p = P.p[i];
     const float inv = P.inv_p[i];
@@ -128,7 +133,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
         for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
           for (int u = 0; u < 4; ++u)
-            acc[pl][u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], bf[cc][s][pl], acc[pl][u], 0, 0, 0);
+            acc[pl][u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b[cc][s][pl], acc[pl][u], 0, 0, 0);
       const int pt = 16 * cbk + (lane & 15);
       int8_t *dst = V + ((((size_t)(tau >> 4) * (P.n * P.P2) + (i * P.P2 + pt)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64 + g * 16;
       if (WIDE) {
@@ -162,14 +167,10 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
         if (pt < P.P2) *(v4i *)dst = out;
       }
     }
-    if (more) {
-#pragma unroll
-      for (int cc = 0; cc < K1_CPW; ++cc)
-#pragma unroll
-        for (int s = 0; s < KS1; ++s)
-#pragma unroll
-          for (int pl = 0; pl < PL; ++pl) bf[cc][s][pl] = bn[cc][s][pl];
-    }
+  };
+  for (int step = 0; step < nsteps; step += 2) {
+    do_step(step, bf, bn);
+    if (step + 1 < nsteps) do_step(step + 1, bn, bf);
   }
 }
 

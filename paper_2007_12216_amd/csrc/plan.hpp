@@ -53,6 +53,7 @@ struct rnswino_plan_s {
   uint32_t crt_inv[8];                      // (prod_{l != i} m_l)^-1 mod m_i
   uint32_t prod_mod32;                      // prod m_i mod 2^32
   int device;                               // HIP device the tables live on, -1 for host-only plans
+  int n_cus;                                // compute units of that device (0 if unknown)
   void *d_tables;                           // one device allocation holding every table below
   size_t d_tables_bytes;
   // offsets (bytes) into d_tables

@@ -84,11 +84,12 @@ inline void launch(Kern kern, dim3 grid, hipStream_t st, Timing tm, Args... args
 
 // ---- K1 ----
 template <bool WIDE>
-void launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
+void launch_k1(const rnswino_plan_t *plan, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
+  const Dims &d = plan->dims;
+  const long long units = (long long)d.T * (d.Cp / 64);
   // x: multiple of 8 (see xcd_chunked()); y: one block per residue, or one block for all residues when there are
   // enough units to fill the chip (the pixel gather is then done once instead of n times; measured on the VGG16
   // stack, two blocks per CU are already enough for that to win)
-  const long long units = (long long)d.T * (d.Cp / 64);
   const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)(units >= 512 ? 1 : d.n));
   switch (d.KS1) {
     case 1: launch(k1_input_transform<1, WIDE>, grid, st, tm, P, x, V); break;
@@ -217,7 +218,7 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
     t2.start = (hipEvent_t)events[2]; t2.stop = (hipEvent_t)events[3];
     t3.start = (hipEvent_t)events[4]; t3.stop = (hipEvent_t)events[5];
   }
-  if (d.wide) launch_k1<true>(d, P, x_dev, Vp, st, t1); else launch_k1<false>(d, P, x_dev, Vp, st, t1);
+  if (d.wide) launch_k1<true>(plan, P, x_dev, Vp, st, t1); else launch_k1<false>(plan, P, x_dev, Vp, st, t1);
   if (d.wide) launch_k2<true>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2); else launch_k2<false>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2);
   if (d.wide) launch_k3<true>(d, P, Op, y_dev, st, t3); else launch_k3<false>(d, P, Op, y_dev, st, t3);
   return launch_status();
@@ -238,6 +239,7 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   if (!pl) return RNSWINO_E_INVALID;
   pl->desc = *desc;
   pl->device = -1;
+  pl->n_cus = 0;
   pl->d_tables = nullptr;
   pl->d_tables_bytes = 0;
   int rc = validate_desc(*desc, pl->dims);
@@ -270,6 +272,11 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
       (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP;
     }
     pl->device = dev;
+    {
+      int cus = 0;
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) pl->n_cus = cus;
+      else (void)hipGetLastError();
+    }
   }
   *out = pl;
   return RNSWINO_OK;
