@@ -220,8 +220,8 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
 // once per block in LDS, and every wave walks over units = (k, block of 16 tiles) with a grid stride, loading the O
 // operand of its next unit while the current one is multiplied and converted.  Per unit a wave issues only its own
 // O loads (no table reads from global memory, no copies of O in other waves); the table fragments come from LDS.
-// Grid: min(ceil(units / 4), K3_STREAM_BLOCKS) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
-constexpr int K3_STREAM_BLOCKS = 1024;
+// Grid: min(ceil(units / 4), three blocks per CU) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
+constexpr int K3_STREAM_BLOCKS = 768;   // three resident blocks per CU (register budget) on 256 CUs
 
 template <int NRES, int KS3>
 __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const uint32_t *__restrict__ O,
@@ -261,12 +261,11 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
     }
   };
 
-  v4i cur[NRES][KS3], nxt[NRES][KS3];
-  load_o(unit, cur);
-  for (; unit < nunits; unit += nwaves) {
-    const bool more = unit + nwaves < nunits;
-    if (more) load_o(unit + nwaves, nxt);
-    const int k = unit / ntb, tau = (unit - k * ntb) * 16 + (lane & 15);
+  // One unit with its O operand in `o`, while the operand of the wave's next unit travels into `onext`; the loop
+  // alternates the two register sets (a copy would wait for every memory operation issued before it).
+  auto do_unit = [&](int u, v4i (&o)[NRES][KS3], v4i (&onext)[NRES][KS3]) {
+    if (u + nwaves < nunits) load_o(u + nwaves, onext);
+    const int k = u / ntb, tau = (u - k * ntb) * 16 + (lane & 15);
     const TilePos tp = tile_position(P, k, tau);
     for (int rb = 0; rb < P.RB3; ++rb) {
       uint32_t w[NRES][4];
@@ -276,7 +275,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
 #pragma unroll
         for (int s = 0; s < KS3; ++s) {
           const v4i a = *(const v4i *)(ka_lds + (((i * P.RB3 + rb) * KS3) + s) * 1024 + lane * 16);
-          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, cur[i][s], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, o[i][s], acc, 0, 0, 0);
         }
         // |acc| <= t*t * 126 * 127 < 2^24; residue shifted by +p so that it is non-negative
 #pragma unroll
@@ -284,12 +283,13 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
       }
       k3_convert_and_store<NRES>(P, w, rb, g, tp, y);
     }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < NRES; ++i)
-#pragma unroll
-        for (int s = 0; s < KS3; ++s) cur[i][s] = nxt[i][s];
-    }
+  };
+  v4i oa[NRES][KS3], ob[NRES][KS3];
+  load_o(unit, oa);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the loop is entered with nothing pending
+  for (; unit < nunits; unit += 2 * nwaves) {
+    do_unit(unit, oa, ob);
+    if (unit + nwaves < nunits) do_unit(unit + nwaves, ob, oa);
   }
 }
 

@@ -151,9 +151,9 @@ void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t 
 
 // streaming variant: 8-bit moduli, table of all residues at most 64 KiB, n * KS3 <= 8 (O operand in registers twice)
 template <int NRES, int KS3>
-void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
   const long long blocks = ((long long)d.K * (d.Tp / 16) + 3) / 4;
-  const dim3 grid((unsigned)(blocks < K3_STREAM_BLOCKS ? blocks : K3_STREAM_BLOCKS));
+  const dim3 grid((unsigned)(blocks < max_blocks ? blocks : max_blocks));
   const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
   if (tm.start || tm.stop)
     hipExtLaunchKernelGGL((k3_inverse_crt_stream<NRES, KS3>), grid, dim3(256), lds, st, tm.start, tm.stop, 0, P, O, y);
@@ -166,23 +166,24 @@ inline bool k3_stream_applies(const Dims &d) {
          (long long)d.K * (d.Tp / 16) >= 4LL * K3_STREAM_BLOCKS;
 }
 
-void launch_k3_stream(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+void launch_k3_stream(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
   switch (d.n * 10 + d.KS3) {
-    case 11: launch_k3_stream_one<1, 1>(d, P, O, y, st, tm); break;
-    case 12: launch_k3_stream_one<1, 2>(d, P, O, y, st, tm); break;
-    case 21: launch_k3_stream_one<2, 1>(d, P, O, y, st, tm); break;
-    case 22: launch_k3_stream_one<2, 2>(d, P, O, y, st, tm); break;
-    case 31: launch_k3_stream_one<3, 1>(d, P, O, y, st, tm); break;
-    case 32: launch_k3_stream_one<3, 2>(d, P, O, y, st, tm); break;
-    case 41: launch_k3_stream_one<4, 1>(d, P, O, y, st, tm); break;
-    default: launch_k3_stream_one<4, 2>(d, P, O, y, st, tm); break;
+    case 11: launch_k3_stream_one<1, 1>(d, P, O, y, max_blocks, st, tm); break;
+    case 12: launch_k3_stream_one<1, 2>(d, P, O, y, max_blocks, st, tm); break;
+    case 21: launch_k3_stream_one<2, 1>(d, P, O, y, max_blocks, st, tm); break;
+    case 22: launch_k3_stream_one<2, 2>(d, P, O, y, max_blocks, st, tm); break;
+    case 31: launch_k3_stream_one<3, 1>(d, P, O, y, max_blocks, st, tm); break;
+    case 32: launch_k3_stream_one<3, 2>(d, P, O, y, max_blocks, st, tm); break;
+    case 41: launch_k3_stream_one<4, 1>(d, P, O, y, max_blocks, st, tm); break;
+    default: launch_k3_stream_one<4, 2>(d, P, O, y, max_blocks, st, tm); break;
   }
 }
 
 template <bool WIDE>
-void launch_k3(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+void launch_k3(const rnswino_plan_t *plan, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
+  const Dims &d = plan->dims;
   if (!WIDE && k3_stream_applies(d)) {   // many units: table in LDS, waves stream over the units
-    launch_k3_stream(d, P, O, y, st, tm);
+    launch_k3_stream(d, P, O, y, plan->n_cus > 0 ? 3 * plan->n_cus : K3_STREAM_BLOCKS, st, tm);
     return;
   }
   switch (d.n) {
@@ -220,7 +221,7 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
   }
   if (d.wide) launch_k1<true>(plan, P, x_dev, Vp, st, t1); else launch_k1<false>(plan, P, x_dev, Vp, st, t1);
   if (d.wide) launch_k2<true>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2); else launch_k2<false>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2);
-  if (d.wide) launch_k3<true>(d, P, Op, y_dev, st, t3); else launch_k3<false>(d, P, Op, y_dev, st, t3);
+  if (d.wide) launch_k3<true>(plan, P, Op, y_dev, st, t3); else launch_k3<false>(plan, P, Op, y_dev, st, t3);
   return launch_status();
 }
 
