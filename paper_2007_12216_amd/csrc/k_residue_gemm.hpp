@@ -13,8 +13,7 @@
 //   sum U V = 65536 sum(Uh Vh) + 256 sum(Uh Vl + Ul Vh) + sum(Ul Vl):
 // four int8 MFMAs into three accumulators, combined in 64 bits and reduced once at the end.
 //
-// Grid: x = n*Q rounded up to a multiple of 8, y = ceil(Kp / (16*RM)), z = ceil(Tp / (16*NTB)).  Workgroups are handed to the
-// 8 XCDs round-robin by linear id, so with gridDim.x a multiple of 8 all blocks of one x (which read the same V) share an L2.
+// Grid: one-dimensional, 8 * (ceil(n*Q / 8) rounded up to a multiple of xgroup) * ceil(Kp / (16*RM)) * ceil(Tp / (16*NTB)).
 #pragma once
 #include <type_traits>
 
@@ -24,7 +23,7 @@ namespace rnswino {
 
 template <int KS, int NTB, int RM, bool WIDE>
 __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *__restrict__ U,
-                                                        const int8_t *__restrict__ V, uint32_t *__restrict__ O) {
+                                                        const int8_t *__restrict__ V, uint32_t *__restrict__ O, int xgroup) {
   constexpr int PL = WIDE ? 2 : 1;
   constexpr int NACC = WIDE ? 3 : 1;
   constexpr int COLS = 16 * NTB;
@@ -34,11 +33,24 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
   __shared__ __attribute__((aligned(16))) uint32_t tile[ROWS * PITCH];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: slab addresses stay scalar
   const int lane = threadIdx.x & 63;
-  if (blockIdx.x >= P.n * P.Q) return;             // grid.x is padded to a multiple of 8 (one XCD per x residue class)
-  const int i = blockIdx.x / P.Q, q = blockIdx.x % P.Q;
-  const int pt = 4 * q + wave;
   const int nkb = P.Kp >> 4, ntb = P.Tp >> 4, ncb = P.Cp >> 6;
-  const int kb0 = blockIdx.y * RM, tb0 = blockIdx.z * NTB;
+  // Work item (x = residue and point group, y = row block, z = tile block) from the linear workgroup id.  Workgroups
+  // are handed to the 8 XCDs round-robin by id, so x = 8 * (...) + id % 8 keeps one x on one XCD.  Within an XCD the
+  // ids run over `xgroup` values of x first, then y, then z, then the groups of x: the workgroups that share a slice
+  // of U (same x and y, along z) or of V (same x and z, along y) follow each other closely enough to find it in the
+  // XCD's L2, while `xgroup` different x at a time spread the accesses over the L2's channels.
+  const int gy = (nkb + RM - 1) / RM, gz = (ntb + NTB - 1) / NTB;
+  int rest = blockIdx.x >> 3;
+  const int xi = rest % xgroup;
+  rest /= xgroup;
+  const int by = rest % gy;
+  rest /= gy;
+  const int bz = rest % gz;
+  const int bx = ((rest / gz) * xgroup + xi) * 8 + (blockIdx.x & 7);
+  if (bx >= P.n * P.Q) return;                     // x is padded to a multiple of 8
+  const int i = bx / P.Q, q = bx % P.Q;
+  const int pt = 4 * q + wave;
+  const int kb0 = by * RM, tb0 = bz * NTB;
   const int p = P.p[i];
   const float inv = P.inv_p[i];
 

@@ -104,10 +104,18 @@ void launch_k1(const rnswino_plan_t *plan, const KParams &P, const int8_t *x, in
 // in flight, limited by the register budget of the variant.
 template <int KS, int NTB, int RM, bool WIDE>
 void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
-  // x padded to a multiple of 8 so that the blocks of one (residue, point group), which share V, run on one XCD
-  const dim3 grid((unsigned)((d.n * d.Q + 7) / 8 * 8), (unsigned)((d.Kp + 16 * RM - 1) / (16 * RM)),
-                  (unsigned)((d.Tp / 16 + NTB - 1) / NTB));
-  launch(k2_residue_gemm<KS, NTB, RM, WIDE>, grid, st, tm, P, U, V, O);
+  // One-dimensional grid: the kernel derives (x, row block, tile block) from the id in an order that suits the L2s.
+  // A slice of U is used again after xgroup * gy workgroups of its XCD, which meanwhile touch xgroup * (U of one x +
+  // about two tile-block slices of V): xgroup is the largest count for which that stays within 3 of the L2's 4 MiB.
+  const long long pl = WIDE ? 2 : 1;
+  const long long nxh = (d.n * d.Q + 7) / 8, gy = (d.Kp + 16 * RM - 1) / (16 * RM), gz = (d.Tp / 16 + NTB - 1) / NTB;
+  const long long u_x = 4LL * d.Kp * d.Cp * pl, v_slice = 4LL * 16 * NTB * d.Cp * pl;
+  long long xgroup = gz == 1 ? nxh : (3LL << 20) / (u_x + 2 * v_slice);
+  xgroup = xgroup < 1 ? 1 : (xgroup > nxh ? nxh : xgroup);
+  if (xgroup > 1 && xgroup < nxh && (xgroup & 1) == 0) --xgroup;   // measured: even group sizes run into each other in the L2 channels
+  const long long blocks = 8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz;
+  const dim3 grid((unsigned)blocks);
+  launch(k2_residue_gemm<KS, NTB, RM, WIDE>, grid, st, tm, P, U, V, O, (int)xgroup);
 }
 
 template <int NTB, bool WIDE>
