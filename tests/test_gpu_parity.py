@@ -237,6 +237,45 @@ def test_fused_requant_refuses_unsupported_tiles():
     assert e.value.code == -2
 
 
+NETWORK_CASES = [
+    # synthetic stand-ins with the shapes of other networks' stride-1 layers (the paper's Tables 4 and 5 name ResNet50's
+    # 3x3 layers and Inception-v3's 5x5 layer); seeded uniform int8 values, batch 2
+    # name, N, C, K, H, W, r, m, pad, moduli
+    ("resnet 3x3 64->64 56x56", 2, 64, 64, 56, 56, 3, 8, 1, (251, 241, 239, 233)),
+    ("resnet 3x3 128->128 28x28", 2, 128, 128, 28, 28, 3, 8, 1, (251, 241, 239, 233)),
+    ("resnet 3x3 256->256 14x14", 2, 256, 256, 14, 14, 3, 8, 1, (251, 241, 239, 233)),
+    ("resnet 3x3 512->512 7x7", 2, 512, 512, 7, 7, 3, 6, 1, (251, 241, 239, 233)),
+    ("resnet 3x3 256->256 14x14, 16-bit moduli", 1, 256, 256, 14, 14, 3, 14, 1, (65521, 65519)),
+    ("inception 5x5 48->64 35x35, F(12,5)", 2, 48, 64, 35, 35, 5, 12, 2, (251, 241, 239, 233)),
+    ("inception 5x5 48->64 35x35, F(4,5)", 2, 48, 64, 35, 35, 5, 4, 2, (251, 241, 239, 233)),
+]
+
+
+@pytest.mark.parametrize("case", NETWORK_CASES, ids=[c[0] for c in NETWORK_CASES])
+def test_other_networks_layer_shapes(case):
+    name, N, C, K, H, W, r, m, pad, moduli = case
+    print("network shape", name, flush=True)
+    x = si.int8_tensor(7100 + N * C + H, (N, C, H, W))
+    w = si.int8_tensor(7200 + K + r, (K, C, r, r))
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    assert np.array_equal(y, direct_conv2d(x, w, pad))
+
+
+def test_tile_selection_times_every_candidate_and_keeps_the_fastest():
+    """Per-layer choice of the output tile (section 6), measured instead of counted; the chosen tile computes the
+    same exact result as any other."""
+    from paper_2007_12216_amd import select
+    print("tile selection", flush=True)
+    N, C, K, H, W, r, pad, moduli = 1, 64, 64, 28, 28, 3, 1, (251, 241, 239, 233)
+    best, times = select.select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=(4, 6, 8, 14), iters=5)
+    assert set(times) == {4, 6, 8, 14} and best in times and times[best] == min(times.values())
+    assert all(0.0 < t < 1e5 for t in times.values())
+    x = si.int8_tensor(7301, (N, C, H, W))
+    w = si.int8_tensor(7302, (K, C, r, r))
+    _, y = run_layer(N, C, K, H, W, r, best, pad, moduli, x, w)
+    assert np.array_equal(y, direct_conv2d(x, w, pad))
+
+
 def _random_cases(count, seed):
     """Seeded random layer shapes covering odd sizes, every filter size up to 7, 1..8 moduli of both widths."""
     rng = np.random.default_rng(seed)

@@ -123,3 +123,17 @@ def test_host_only_plan_cannot_execute():
     with pytest.raises(rn.RnsWinoError) as e:
         rn.rnswino_conv2d(plan, buf, buf, buf, buf)
     assert e.value.code == -7
+
+
+def test_tile_candidates_and_table2_count():
+    """Host side of the per-layer tile choice (section 6): which output tiles a moduli set admits, and the
+    multiplication count m^2 r^2 / (t^2 n) of Table 2."""
+    from paper_2007_12216_amd import select
+    assert select.candidate_tiles(3, (251, 241, 239, 233)) == list(range(2, 15))
+    # composite moduli 253 = 11*23 and 247 = 13*19 drop out once point differences reach 11 (section 5)
+    assert select.candidate_tiles(3, (253, 251, 247)) == list(range(2, 11))
+    assert select.candidate_tiles(5, (251, 241, 239, 233)) == list(range(2, 13))
+    # Table 2 of the paper, three moduli: F(8,3) 1.92, F(10,3) 2.08, F(12,5) 4.69, F(14,3) 2.30
+    for (m, r), printed in {(8, 3): 1.92, (10, 3): 2.08, (12, 5): 4.69, (14, 3): 2.30}.items():
+        assert abs(select.multiplication_reduction(m, r, 3) - printed) < 0.01
+    assert abs(select.multiplication_reduction(8, 3, 4) - 1.44) < 1e-9
