@@ -92,7 +92,7 @@ __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uin
   const float inv_m = 1.0f / (float)m;
   const int o0 = 16 * rb + 4 * g;
   if (P.epi != 0) {
-    // host guarantees m in {4, 8}, Wo % 4 == 0, even Ho and Wo when pooling
+    // host guarantees m in {4, 8}, even Wo; when pooling Wo % 4 == 0 and even Ho
     const int u = (int)(((float)o0 + 0.5f) * inv_m);
     const int v = o0 - u * m;
     const bool inside = tp.ok && o0 < mm && tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo;
@@ -100,7 +100,14 @@ __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uin
       uint32_t packed = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) packed |= ((uint32_t)min(127, max(-128, val[j] >> P.shift)) & 0xFFu) << (8 * j);
-      if (inside) *(uint32_t *)(P.act + tp.origin + (uint32_t)(u * P.Wo + v)) = packed;
+      int8_t *dst = P.act + tp.origin + (uint32_t)(u * P.Wo + v);
+      if ((P.Wo & 3) == 0) {
+        if (inside) *(uint32_t *)dst = packed;
+      } else {
+        // Wo even but not a multiple of 4: rows are only 2-byte aligned, and the second half may hang over the edge
+        if (inside) *(uint16_t *)dst = (uint16_t)packed;
+        if (inside && tp.ox0 + v + 2 < P.Wo) *(uint16_t *)(dst + 2) = (uint16_t)(packed >> 16);
+      }
     } else {
       // rows u and u+1 (u even) of an output tile sit in lanes l and l ^ 4m (m = 8: 32 apart, m = 4: 16 apart)
       const int h0 = max(val[0], val[1]), h1 = max(val[2], val[3]);

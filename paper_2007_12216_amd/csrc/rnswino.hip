@@ -334,7 +334,7 @@ int rnswino_conv2d_requant(const rnswino_plan_t *plan, const int8_t *x_dev, cons
                            int32_t shift, int32_t pool, void *workspace_dev, void *stream) {
   if (!plan || shift < 0 || shift > 31) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
-  if ((d.m != 4 && d.m != 8) || (d.Wo & 3) || (pool && ((d.Ho | d.Wo) & 1))) return RNSWINO_E_UNSUPPORTED;
+  if ((d.m != 4 && d.m != 8) || (d.Wo & 1) || (pool && ((d.Wo & 3) || (d.Ho & 1)))) return RNSWINO_E_UNSUPPORTED;
   return conv2d_impl(plan, x_dev, U_dev, nullptr, workspace_dev, stream, nullptr, pool ? 2 : 1, shift, a_dev);
 }
 

@@ -207,11 +207,12 @@ def test_vgg16_stack_full_size():
     assert np.array_equal(y.cpu().numpy(), ref_y)
 
 
-@pytest.mark.parametrize("m,pool", [(8, False), (8, True), (4, False), (4, True)])
-def test_fused_requant_matches_the_oracle_glue(m, pool):
+@pytest.mark.parametrize("m,pool,W", [(8, False, 28), (8, True, 28), (4, False, 28), (4, True, 28),
+                                      (8, False, 14), (4, False, 30), (8, False, 22)])   # rows not a multiple of 4 bytes
+def test_fused_requant_matches_the_oracle_glue(m, pool, W):
     from oracle import requant_shift_clamp, maxpool2x2
-    print("fused requant", m, pool, flush=True)
-    N, C, K, H, W, r, pad, moduli, shift = 2, 20, 24, 20, 28, 3, 1, (251, 241, 239), 10
+    print("fused requant", m, pool, W, flush=True)
+    N, C, K, H, r, pad, moduli, shift = 2, 20, 24, 20, 3, 1, (251, 241, 239), 10
     x = si.int8_tensor(401, (N, C, H, W))
     w = si.int8_tensor(402, (K, C, r, r))
     from paper_2007_12216_amd.layer import ConvLayer
