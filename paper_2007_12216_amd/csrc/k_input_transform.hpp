@@ -9,10 +9,11 @@
 // 16 consecutive pixels of one image row: one unaligned 16-byte load, masked where the tile hangs over the
 // image border (zero padding and ragged last tiles).
 //
-// Block = (tile, block of 64 channels, residue): its 64 x t x 16 pixel patch is gathered once into LDS (the
-// gather of 16-byte row segments is what costs; sharing it between the four waves pays), then each wave takes
-// every fourth group of K1_CPW column blocks.  Accumulator rows are channels 4g+j, so the four channel groups u
-// give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
+// Block = (tile, block of 64 channels, one residue or all of them): its 64 x t x 16 pixel patch is gathered once into
+// LDS (the gather of 16-byte row segments is what costs; sharing it between the four waves pays), then each wave
+// walks over its steps (residue, every fourth group of K1_CPW column blocks), the table fragments of the next
+// step in flight while the current one is multiplied.  Accumulator rows are channels 4g+j, so the four channel
+// groups u give one lane exactly the 16 bytes of V it has to store (channel order of layout.hpp).
 // 16-bit moduli: the table has a high and a low byte plane, V = (256 * sum_h + sum_l) mod p, stored as two planes.
 // Grid: x = T * Cp/64 rounded up to a multiple of 8 (see xcd_chunked), y = n (one residue per block) or 1 (the block
 // walks over all residues with the same gathered patch); 256 threads; 64 * (4*KS1 + 1) * 16 bytes of LDS.

@@ -10,12 +10,14 @@
 // w_i is the CRT coefficient of residue i and
 //     y = sum_i (P/p_i) w_i - P * rint(sum_i w_i / p_i)        (computed modulo 2^32)
 // is the representative of the result in [-(P-1)/2, (P-1)/2] -- the same value mixed-radix conversion with
-// symmetric digits yields; any representative of w_i gives the same y.  The rounding is done in binary64:
-// sum_i w_i/p_i = y/P + integer with |y/P| <= 1/2 - 1/(2P), and the error of the sum is below 1e-14 while
-// 1/(2P) > 1e-10 for every moduli set whose product can matter for a 32-bit result.
+// symmetric digits yields; any representative of w_i gives the same y.  sum_i w_i/p_i = y/P + integer with
+// |y/P| <= 1/2 - 1/(2P).  The rounding is done in binary64 (error of the sum below 1e-14, while 1/(2P) > 1e-10 for
+// every moduli set whose product can matter for a 32-bit result), or in binary32 when the layer's worst case
+// 2^14 r^2 C keeps |y/P| below 0.45 (the host decides: KParams::quot32).
 //
 // Block = one unit of 16 consecutive (k, tile) pairs and four 16-output row blocks rb = 4*blockIdx.y + wave; every
-// wave loads the O operand itself (the copies hit in L1).  No LDS.
+// wave loads the O operand itself (the copies hit in L1): a wave-uniform row of O plus a 32-bit lane offset per
+// word.  No LDS.
 // Grid: x = ceil(K*T/16) rounded up to a multiple of 8, y = ceil(RB3/4); 256 threads.
 // 16-bit moduli: table and O are two byte planes each; three accumulators as in the GEMM.
 #pragma once
