@@ -88,6 +88,23 @@ def test_extreme_values(xv, wv):
     assert abs(int(ref[0, 0, 5, 5])) == abs(xv * wv) * 9 * C
 
 
+@pytest.mark.parametrize("C,K,moduli,xv,wv", [(2100, 16, (251, 241, 239, 233), -128, -128),
+                                              (2100, 16, (251, 241, 239, 233), -128, 127),
+                                              (2100, 16, (65521, 65519), -128, -128),
+                                              (70, 1030, (251, 241, 239, 233), 127, -128)])
+def test_long_sums_with_extreme_values(C, K, moduli, xv, wv):
+    """Accumulator headroom of the GEMM (reduced every 512 channels for 8-bit moduli, three byte-plane accumulators for
+    16-bit ones) with every product at its largest magnitude, and a K that leaves a ragged last row block."""
+    print("long sums", C, K, moduli, xv, wv, flush=True)
+    N, H, W, r, m, pad = 1, 8, 8, 3, 6, 1
+    x = np.full((N, C, H, W), xv, dtype=np.int8)
+    w = np.full((K, C, r, r), wv, dtype=np.int8)
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    ref = direct_conv2d(x, w, pad)
+    assert np.array_equal(y, ref)
+    assert int(ref[0, 0, 4, 4]) == xv * wv * 9 * C
+
+
 @pytest.mark.parametrize("C,moduli,sign", [(49, (251, 241, 239), 1), (49, (251, 241, 239), -1),
                                            (16, (251, 241, 239), 1), (512, (65521, 65519), -1)])
 def test_results_at_the_edge_of_the_dynamic_range(C, moduli, sign):
