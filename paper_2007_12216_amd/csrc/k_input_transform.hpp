@@ -56,25 +56,41 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
     const long long total = (long long)P.N * P.C * P.H * P.W;
     // byte index of (channel cb*64, row y0, column x0) of this image: block-uniform; a task adds 32 bits to it
     const long long patch0 = (((long long)img * P.C + cb * 64) * P.H + y0) * P.W + x0;
-    for (int task = threadIdx.x; task < 64 * ROWS; task += 256) {
+    // A thread's NT row segments are requested together and only then masked and written to LDS (one after the
+    // other, each load would be waited for in turn: three memory latencies instead of one).
+    constexpr int NT = (64 * ROWS + 255) / 256;
+    v4i val[NT];
+    long long b0[NT];
+    int state[NT];                                     // 0: nothing to load, 1: plain 16-byte load, 2: tensor edge
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int task = threadIdx.x + 256 * k;
       const int c = task / ROWS, a = task - c * ROWS;
       const int gc = cb * 64 + c, gy = y0 + a;
-      v4i val = (v4i){0, 0, 0, 0};
-      if (gc < P.C && a < P.t && gy >= 0 && gy < P.H) {
-        const long long b0 = patch0 + (c * P.H + a) * P.W;      // 64 * H * W stays far below 2^31
-        if (b0 >= 0 && b0 + 16 <= total) {
-          __builtin_memcpy(&val, x + b0, 16);          // one unaligned 16-byte load
-        } else {                                       // first / last bytes of the tensor
-          uint32_t wv[4] = {0, 0, 0, 0};
-          for (int b = 0; b < 16; ++b) {
-            const long long o = b0 + b;
-            if (o >= 0 && o < total) wv[b >> 2] |= (uint32_t)(uint8_t)x[o] << (8 * (b & 3));
-          }
-          val = (v4i){(int)wv[0], (int)wv[1], (int)wv[2], (int)wv[3]};
+      val[k] = (v4i){0, 0, 0, 0};
+      b0[k] = patch0 + (c * P.H + a) * P.W;            // 64 * H * W stays far below 2^31
+      state[k] = 0;
+      if (task < 64 * ROWS && gc < P.C && a < P.t && gy >= 0 && gy < P.H)
+        state[k] = (b0[k] >= 0 && b0[k] + 16 <= total) ? 1 : 2;
+      if (state[k] == 1) __builtin_memcpy(&val[k], x + b0[k], 16);      // one unaligned 16-byte load
+    }
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      if (state[k] == 2) {                             // first / last bytes of the tensor
+        uint32_t wv[4] = {0, 0, 0, 0};
+        for (int b = 0; b < 16; ++b) {
+          const long long o = b0[k] + b;
+          if (o >= 0 && o < total) wv[b >> 2] |= (uint32_t)(uint8_t)x[o] << (8 * (b & 3));
         }
-        val[0] &= cmask[0]; val[1] &= cmask[1]; val[2] &= cmask[2]; val[3] &= cmask[3];
+        val[k] = (v4i){(int)wv[0], (int)wv[1], (int)wv[2], (int)wv[3]};
       }
-      *(v4i *)(xs + c * CROW + a * 16) = val;
+    }
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int task = threadIdx.x + 256 * k;
+      const int c = task / ROWS, a = task - c * ROWS;
+      val[k][0] &= cmask[0]; val[k][1] &= cmask[1]; val[k][2] &= cmask[2]; val[k][3] &= cmask[3];
+      if (task < 64 * ROWS) *(v4i *)(xs + c * CROW + a * 16) = val[k];
     }
   }
   // This wave's work: steps (residue i, column-block group cg) with cg = wave, wave + 4, ...  The table fragments
