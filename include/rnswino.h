@@ -150,6 +150,18 @@ int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, in
 /* Copy one transform matrix (which = RNSWINO_MATRIX_*, modulus_idx < n_moduli) to host_out (row-major int32). */
 int rnswino_plan_get_matrix(const rnswino_plan_t *plan, int which, int modulus_idx, int32_t *host_out);
 
+/* Copy the Kronecker table of one modulus, as the kernels read it, to host_out: which = RNSWINO_TABLE_INPUT is
+ * (B^T kron B^T) mod p (input transform, section 5: V = B^T d B) as int8 [CB][KS1][planes][64 lanes][16]: fragment (cb, s)
+ * holds, for lane l and byte b, the entry of transform point 16 cb + l%16 and tile pixel (row 4 s + l/16, column b), zero
+ * outside the t x t tile; which = RNSWINO_TABLE_INVERSE is (A^T kron A^T) (P/p)^-1 mod p (inverse transform folded with
+ * the CRT factor, sections 3 and 5) as int8 [RB][KS3][planes][64][16]: fragment (rb, s), lane l, byte b = output
+ * 16 rb + l%16 and transform point 64 s + 16 (l/16) + b.  CB = ceil(t^2/16), KS1 = ceil(t/4), RB = ceil(m^2/16),
+ * KS3 = ceil(t^2/64); planes = 1 (8-bit moduli: the symmetric residue) or 2 (16-bit moduli: high byte plane, then low
+ * byte plane, entry = 256 h + l).  Returns the number of bytes (copied only if capacity suffices), or a negative code. */
+#define RNSWINO_TABLE_INPUT 0
+#define RNSWINO_TABLE_INVERSE 1
+int64_t rnswino_plan_get_table(const rnswino_plan_t *plan, int which, int modulus_idx, int8_t *host_out, size_t capacity);
+
 /* Mixed-radix constant: inverse of moduli[l] modulo moduli[j] (l < j), in [0, moduli[j]). */
 int rnswino_plan_get_mrc_inverse(const rnswino_plan_t *plan, int l, int j, uint32_t *host_out);
 

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = (
     "rnswino_workspace_bytes", "rnswino_filter_transform", "rnswino_conv2d", "rnswino_conv2d_requant",
     "rnswino_conv2d_events",
     "rnswino_requant_pool",
-    "rnswino_plan_get_matrix", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
+    "rnswino_plan_get_matrix", "rnswino_plan_get_table", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
     "rnswino_debug_stage", "rnswino_strerror",
 )
 
@@ -74,6 +74,8 @@ def lib():
         L.rnswino_requant_pool.restype = ctypes.c_int
         L.rnswino_plan_get_matrix.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
         L.rnswino_plan_get_matrix.restype = ctypes.c_int
+        L.rnswino_plan_get_table.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t]
+        L.rnswino_plan_get_table.restype = ctypes.c_int64
         L.rnswino_plan_get_mrc_inverse.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(u32)]
         L.rnswino_plan_get_mrc_inverse.restype = ctypes.c_int
         L.rnswino_plan_dynamic_range.argtypes = [vp]
@@ -187,6 +189,19 @@ def rnswino_plan_get_matrix(plan: Plan, which: int, modulus_idx: int) -> np.ndar
     out = np.zeros(shape, dtype=np.int32)
     _check(lib().rnswino_plan_get_matrix(plan.handle, which, modulus_idx, out.ctypes.data), "rnswino_plan_get_matrix")
     return out
+
+
+TABLE_INPUT, TABLE_INVERSE = 0, 1
+
+
+def rnswino_plan_get_table(plan: Plan, which: int, modulus_idx: int) -> np.ndarray:
+    """Kronecker table of one modulus in the kernels' fragment order: int8 [blocks][steps][planes][64][16]."""
+    n = lib().rnswino_plan_get_table(plan.handle, which, modulus_idx, None, 0)
+    _check(int(min(n, 0)), "rnswino_plan_get_table")
+    out = np.zeros(int(n), dtype=np.int8)
+    _check(int(min(lib().rnswino_plan_get_table(plan.handle, which, modulus_idx, out.ctypes.data, out.nbytes), 0)),
+           "rnswino_plan_get_table")
+    return out.reshape(-1, 64, 16)
 
 
 def rnswino_plan_get_mrc_inverse(plan: Plan, l: int, j: int) -> int:

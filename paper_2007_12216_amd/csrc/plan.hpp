@@ -55,6 +55,7 @@ struct rnswino_plan_s {
   int device;                               // HIP device the tables live on, -1 for host-only plans
   int n_cus;                                // compute units of that device (0 if unknown)
   void *d_tables;                           // one device allocation holding every table below
+  std::vector<char> h_tables;               // the same bytes on the host (query calls)
   size_t d_tables_bytes;
   // offsets (bytes) into d_tables
   size_t off_G;                             // int32 G matrices [n][t*r] (filter transform)

@@ -271,7 +271,7 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   for (int l = 0; l < d.n; ++l)
     for (int j = l + 1; j < d.n; ++j) pl->mrc_inv[l][j] = (uint32_t)mod_inverse(desc->moduli[l], desc->moduli[j]);
 
-  std::vector<char> blob;
+  std::vector<char> &blob = pl->h_tables;
   build_tables(*pl, blob);
   if (!(desc->flags & RNSWINO_FLAG_HOST_ONLY)) {
     int dev = -1;
@@ -364,6 +364,20 @@ int rnswino_plan_get_matrix(const rnswino_plan_t *plan, int which, int modulus_i
   if (!src) return RNSWINO_E_INVALID;
   std::memcpy(host_out, src->data(), src->size() * sizeof(int32_t));
   return RNSWINO_OK;
+}
+
+int64_t rnswino_plan_get_table(const rnswino_plan_t *plan, int which, int modulus_idx, int8_t *host_out, size_t capacity) {
+  if (!plan || modulus_idx < 0 || modulus_idx >= plan->dims.n) return RNSWINO_E_INVALID;
+  const Dims &d = plan->dims;
+  const size_t planes = d.wide ? 2 : 1;
+  size_t per, off;
+  if (which == RNSWINO_TABLE_INPUT) { per = (size_t)d.CB1 * d.KS1 * planes * 1024; off = plan->off_KB; }
+  else if (which == RNSWINO_TABLE_INVERSE) { per = (size_t)d.RB3 * d.KS3 * planes * 1024; off = plan->off_KA; }
+  else return RNSWINO_E_INVALID;
+  off += per * (size_t)modulus_idx;
+  if (off + per > plan->h_tables.size()) return RNSWINO_E_INVALID;
+  if (host_out && capacity >= per) std::memcpy(host_out, plan->h_tables.data() + off, per);
+  return (int64_t)per;
 }
 
 int rnswino_plan_get_mrc_inverse(const rnswino_plan_t *plan, int l, int j, uint32_t *host_out) {

@@ -137,3 +137,54 @@ def test_tile_candidates_and_table2_count():
     for (m, r), printed in {(8, 3): 1.92, (10, 3): 2.08, (12, 5): 4.69, (14, 3): 2.30}.items():
         assert abs(select.multiplication_reduction(m, r, 3) - printed) < 0.01
     assert abs(select.multiplication_reduction(8, 3, 4) - 1.44) < 1e-9
+
+
+@pytest.mark.parametrize("m,r,moduli", [(8, 3, (251, 241, 239, 233)), (10, 3, (253, 251, 247)), (7, 3, (251, 241, 239)),
+                                        (12, 5, (251, 241, 239, 233)), (14, 3, (65521, 65519)), (2, 3, (7, 9))])
+def test_kronecker_tables_against_the_oracle_matrices(m, r, moduli):
+    """The tables the transform kernels multiply with: (B^T kron B^T) mod p for V = B^T d B, and
+    (A^T kron A^T) (P/p)^-1 mod p for Y = A^T O A folded with the CRT factor (sections 3 and 5), entry by entry against
+    the oracle's matrices, including the zero padding the kernels rely on."""
+    from oracle import rnswino as rw
+    t = m + r - 1
+    plan = rn.rnswino_plan(1, 4, 4, 2 * m, 2 * m, r, m, r // 2, moduli, flags=HOST | rn.FLAG_ALLOW_UNCHECKED_RANGE)
+    planes = 2 if moduli[0] > 255 else 1
+    prod = int(np.prod([int(p) for p in moduli], dtype=object))
+    for i, p in enumerate(moduli):
+        AT, G, BT = rw.matrices_mod(m, r, p)
+        AT, BT = np.asarray(AT, dtype=object), np.asarray(BT, dtype=object)
+
+        def entry(frags, block, s, lane, b, nsteps):
+            base = (block * nsteps + s) * planes
+            if planes == 1:
+                return int(frags[base, lane, b])
+            return 256 * int(frags[base, lane, b]) + int(frags[base + 1, lane, b])
+
+        kb = rn.rnswino_plan_get_table(plan, rn.TABLE_INPUT, i)
+        ks1, cb1 = (t + 3) // 4, (t * t + 15) // 16
+        assert kb.shape[0] == cb1 * ks1 * planes
+        for cb in range(cb1):
+            for s in range(ks1):
+                for lane in range(64):
+                    pt, a = 16 * cb + lane % 16, 4 * s + lane // 16
+                    for b in range(16):
+                        got = entry(kb, cb, s, lane, b, ks1)
+                        if pt < t * t and a < t and b < t:
+                            assert (got - int(BT[pt // t][a]) * int(BT[pt % t][b])) % p == 0 and abs(got) <= (p - 1) // 2 + (130 if planes == 2 else 0)
+                        else:
+                            assert got == 0
+        ka = rn.rnswino_plan_get_table(plan, rn.TABLE_INVERSE, i)
+        ks3, rb3 = (t * t + 63) // 64, (m * m + 15) // 16
+        assert ka.shape[0] == rb3 * ks3 * planes
+        inv = rw.modinv((prod // p) % p, p)
+        for rb in range(rb3):
+            for s in range(ks3):
+                for lane in range(64):
+                    o = 16 * rb + lane % 16
+                    for b in range(16):
+                        pt = 64 * s + 16 * (lane // 16) + b
+                        got = entry(ka, rb, s, lane, b, ks3)
+                        if o < m * m and pt < t * t:
+                            assert (got - int(AT[o // m][pt // t]) * int(AT[o % m][pt % t]) * inv) % p == 0
+                        else:
+                            assert got == 0
