@@ -24,7 +24,9 @@ namespace rnswino {
 
 constexpr int K1_CPW = 2;
 
-template <int KS1, bool WIDE>
+// PACK: the layer packs TL tiles into one 64-channel block (plan.hpp): block channel c' holds channel c' % Cq of tile
+// (c' / Cq) * Tg + tau, so every gathered row segment has its own tile origin; everything after the gather is the same.
+template <int KS1, bool WIDE, bool PACK>
 __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_t *__restrict__ x,
                                                            int8_t *__restrict__ V) {
   constexpr int ROWS = 4 * KS1;
@@ -36,41 +38,65 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   const int lane = threadIdx.x & 63, g = lane >> 4;
   const int ncb = P.Cp >> 6;
   const int i0 = gridDim.y == 1 ? 0 : blockIdx.y, i1 = gridDim.y == 1 ? P.n : i0 + 1;   // residues of this block
-  const int unit = xcd_chunked(blockIdx.x, gridDim.x, P.T * ncb);   // neighbouring tiles (shared image lines) on one XCD
+  const int unit = xcd_chunked(blockIdx.x, gridDim.x, P.Tg * ncb);  // neighbouring tiles (shared image lines) on one XCD
   if (unit < 0) return;
-  const int cb = unit % ncb, tau = unit / ncb;
-  const int tx = tau % P.tw, ty = (tau / P.tw) % P.th, img = tau / (P.tw * P.th);
-  const int y0 = ty * P.m - P.pad, x0 = tx * P.m - P.pad;
+  const int cb = unit % ncb, tau = unit / ncb;     // tau: GEMM column (a group of TL tiles when PACK)
   {
-    // columns b of the 16-pixel row segment that lie inside the image and inside the tile: [lo, hi)
-    const int lo = x0 < 0 ? -x0 : 0;
-    const int hi = min(P.t, P.W - x0);
-    uint32_t cmask[4];
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      uint32_t mk = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) mk |= ((4 * d + e) >= lo && (4 * d + e) < hi) ? (0xFFu << (8 * e)) : 0u;
-      cmask[d] = mk;
-    }
     const long long total = (long long)P.N * P.C * P.H * P.W;
-    // byte index of (channel cb*64, row y0, column x0) of this image: block-uniform; a task adds 32 bits to it
-    const long long patch0 = (((long long)img * P.C + cb * 64) * P.H + y0) * P.W + x0;
+    // origin, tile and channel of the row segment that goes to block channel cblk
+    struct Seg { long long base; int y0, x0; bool ok; };
+    auto tile_origin = [&](int tile, int ch) -> Seg {
+      const int trow = tile / P.tw;
+      const int tx = tile - trow * P.tw, img = trow / P.th, ty = trow - img * P.th;
+      Seg sg;
+      sg.y0 = ty * P.m - P.pad;
+      sg.x0 = tx * P.m - P.pad;
+      sg.ok = tile < P.T;
+      sg.base = (((long long)img * P.C + ch) * P.H + sg.y0) * P.W + sg.x0;   // byte index of (ch, row y0, column x0)
+      return sg;
+    };
+    const Seg block_seg = tile_origin(PACK ? 0 : tau, PACK ? 0 : cb * 64);   // not packed: one tile, block-uniform
+    auto segment = [&](int cblk) -> Seg {
+      if (PACK) {
+        Seg sg = tile_origin((cblk / P.Cq) * P.Tg + tau, cblk % P.Cq);
+        sg.ok = sg.ok && (cblk % P.Cq) < P.C;
+        return sg;
+      }
+      Seg sg = block_seg;
+      sg.ok = cb * 64 + cblk < P.C;
+      sg.base += (cblk * P.H) * P.W;               // 64 * H * W stays far below 2^31
+      return sg;
+    };
+    // columns b of the 16-pixel row segment that lie inside the image and inside the tile: [lo, hi)
+    auto column_mask = [&](int x0, uint32_t (&cmask)[4]) {
+      const int lo = x0 < 0 ? -x0 : 0;
+      const int hi = min(P.t, P.W - x0);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        uint32_t mk = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mk |= ((4 * d + e) >= lo && (4 * d + e) < hi) ? (0xFFu << (8 * e)) : 0u;
+        cmask[d] = mk;
+      }
+    };
     // A thread's NT row segments are requested together and only then masked and written to LDS (one after the
     // other, each load would be waited for in turn: three memory latencies instead of one).
     constexpr int NT = (64 * ROWS + 255) / 256;
     v4i val[NT];
     long long b0[NT];
+    int sx0[NT];
     int state[NT];                                     // 0: nothing to load, 1: plain 16-byte load, 2: tensor edge
 #pragma unroll
     for (int k = 0; k < NT; ++k) {
       const int task = threadIdx.x + 256 * k;
       const int c = task / ROWS, a = task - c * ROWS;
-      const int gc = cb * 64 + c, gy = y0 + a;
+      const Seg sg = segment(c);
+      const int gy = sg.y0 + a;
       val[k] = (v4i){0, 0, 0, 0};
-      b0[k] = patch0 + (c * P.H + a) * P.W;            // 64 * H * W stays far below 2^31
+      b0[k] = sg.base + (long long)a * P.W;
+      sx0[k] = sg.x0;
       state[k] = 0;
-      if (task < 64 * ROWS && gc < P.C && a < P.t && gy >= 0 && gy < P.H)
+      if (task < 64 * ROWS && sg.ok && a < P.t && gy >= 0 && gy < P.H)
         state[k] = (b0[k] >= 0 && b0[k] + 16 <= total) ? 1 : 2;
       if (state[k] == 1) __builtin_memcpy(&val[k], x + b0[k], 16);      // one unaligned 16-byte load
     }
@@ -89,6 +115,8 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
     for (int k = 0; k < NT; ++k) {
       const int task = threadIdx.x + 256 * k;
       const int c = task / ROWS, a = task - c * ROWS;
+      uint32_t cmask[4];
+      column_mask(sx0[k], cmask);
       val[k][0] &= cmask[0]; val[k][1] &= cmask[1]; val[k][2] &= cmask[2]; val[k][3] &= cmask[3];
       if (task < 64 * ROWS) *(v4i *)(xs + c * CROW + a * 16) = val[k];
     }

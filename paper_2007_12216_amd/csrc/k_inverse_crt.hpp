@@ -151,19 +151,22 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
   // A unit is 16 consecutive (k, tile) pairs of the flattened K x T index space (no padding tiles: a unit may span
   // several k's).  Workgroups go to the 8 XCDs round-robin by id; neighbouring units share 128-byte lines of O, so
   // each XCD gets one contiguous chunk of the units (grid.x is a multiple of 8).
-  const int npairs = P.K * P.T;                    // below 2^31 (checked when the plan is made)
+  // (For layers that pack TL tiles into a channel block, GEMM row kg = k * TL + tile / Tg and GEMM column tile % Tg.)
+  const int npairs = P.Kg * P.Tg;                  // below 2^31 (checked when the plan is made)
   const int unit = xcd_chunked(blockIdx.x, gridDim.x, (npairs + 15) >> 4);
   if (unit < 0) return;
   const int pair = unit * 16 + (lane & 15);
   const bool pair_ok = pair < npairs;
-  const int k = pair_ok ? pair / P.T : 0;
-  const int tau = pair_ok ? pair - k * P.T : P.T;   // tau = T marks a padding lane (its loads stay inside row k = 0)
+  const int kg = pair_ok ? pair / P.Tg : 0;
+  const int taug = pair_ok ? pair - kg * P.Tg : P.Tg;   // a padding lane's loads stay inside row 0
+  const int k = kg / P.TL;
+  const int tau = pair_ok ? (kg % P.TL) * P.Tg + taug : P.T;   // tau >= T marks a lane without output
 
   // O is [Kp][n][Q][Tp] words (x PL planes) and smaller than 4 GiB: the address of a word is a wave-uniform row
   // (residue, point group 16s + e) plus a 32-bit lane offset (k, lane group 4g, tile).  Point groups >= Q of the
   // last contraction step are clamped to Q - 1: the table is zero there, so whatever is read does not count.
   const uint32_t rowstride = (uint32_t)P.Tp * PL;
-  const uint32_t lane_off = (uint32_t)(k * P.n * P.Q) * rowstride + (uint32_t)tau * PL;
+  const uint32_t lane_off = (uint32_t)(kg * P.n * P.Q) * rowstride + (uint32_t)taug * PL;
   uint32_t voff[KS3][4];
 #pragma unroll
   for (int s = 0; s < KS3; ++s)
@@ -239,7 +242,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: unit arithmetic stays scalar
   const int lane = threadIdx.x & 63, g = lane >> 4;
   const int ntb = P.Tp >> 4;
-  const int nunits = P.K * ntb;                    // below 2^31 (checked when the plan is made)
+  const int nunits = P.Kg * ntb;                   // below 2^31 (checked when the plan is made); rows and columns are the GEMM's
   const int nwaves = gridDim.x * 4;
   {
     const int bytes = NRES * P.RB3 * KS3 * 1024;
@@ -274,7 +277,8 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
   // alternates the two register sets (a copy would wait for every memory operation issued before it).
   auto do_unit = [&](int u, v4i (&o)[NRES][KS3], v4i (&onext)[NRES][KS3]) {
     if (u + nwaves < nunits) load_o(u + nwaves, onext);
-    const int k = u / ntb, tau = (u - k * ntb) * 16 + (lane & 15);
+    const int kg = u / ntb, taug = (u - kg * ntb) * 16 + (lane & 15);
+    const int k = kg / P.TL, tau = taug < P.Tg ? (kg % P.TL) * P.Tg + taug : P.T;   // packed layers: see plan.hpp
     const TilePos tp = tile_position(P, k, tau);
     for (int rb = 0; rb < P.RB3; ++rb) {
       uint32_t w[NRES][4];

@@ -14,7 +14,8 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 struct KParams {
   int N, C, K, H, W, r, m, t, pad;
   int Ho, Wo, th, tw, T, n;
-  int Cp, Kp, Tp, P2, Q;
+  int TL, Cq, Kg, Tg;         // tile packing of layers with few channels (plan.hpp); TL = 1: none
+  int Cp, Kp, Tp, P2, Q;      // GEMM extents (of the packed problem when TL > 1)
   int p[8];
   float inv_p[8];
   double inv_pd[8];           // 1 / p_i

@@ -19,6 +19,8 @@
 //   O  [Kp][n][Q][Tp][4 B]      byte e of the last axis is transform point 4*q + e; k outermost, so that the
 //                               n*Q words the inverse transform needs for one (k, tile) lie in one small region
 //
+// (k, c and tile are the GEMM's row, channel and column: for layers with few channels they are the packed indices
+// described in plan.hpp.)
 // n moduli, t*t transform points, Cp = C rounded up to 64 (padding channels are
 // zero in U), Kp = K rounded up to 16, Tp = T rounded up to 16, Q = ceil(t*t/4).
 // For 16-bit moduli a residue is two signed bytes (value = 256*h + l) kept in two

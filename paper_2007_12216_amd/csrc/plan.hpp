@@ -12,7 +12,13 @@ struct Dims {
   int Ho, Wo, th, tw, T;     // output plane, tiles per image, tiles in total
   int n;                     // number of moduli
   int wide;                  // 0: moduli < 256 (residues in 8 bits), 1: 16-bit moduli
-  int Cp, Kp, Tp;            // C padded to 64, K and T padded to 16 (tiled tensor extents)
+  // Layers with at most 32 channels pack TL = 2..16 neighbouring tiles into one 64-channel block instead of padding
+  // each tile's few channels with zeros.  Tile tau sits in slot tau / Tg of GEMM column tau % Tg (consecutive columns are
+  // consecutive tiles): GEMM channel c' = slot * Cq + c, GEMM row k' = k * TL + slot (the transformed filter is
+  // block-diagonal in the slot).  Same products, same sums, 1/TL of the transformed-input bytes.  TL = 1, Cq = 64 otherwise.
+  int TL, Cq;                // tiles per 64-channel block, channel slots per tile (TL * Cq = 64 when TL > 1)
+  int Kg, Tg;                // GEMM rows K * TL and GEMM columns ceil(T / TL)
+  int Cp, Kp, Tp;            // GEMM extents of the tiled tensors: channels padded to 64, Kg and Tg padded to 16
   int P2;                    // t*t transform points
   int Q;                     // ceil(t*t / 4): groups of four transform points in the O tensor
   int CB1, KS1;              // input transform on MFMA: 16-point column blocks ceil(t*t/16), contraction steps ceil(t/4)

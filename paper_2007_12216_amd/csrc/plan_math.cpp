@@ -165,9 +165,21 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   o.T = (int)T;
   o.n = d.n_moduli;
   o.wide = n16 ? 1 : 0;
+  o.TL = 1;
+  o.Cq = 64;
+  if (d.C <= 32) {
+    int cq = 4;
+    while (cq < d.C) cq *= 2;
+    int tl = 64 / cq;
+    while (tl > 1 && o.T < 16 * tl) tl /= 2;      // not worth it before the packed tiles fill a 16-column block
+    o.TL = tl;
+    o.Cq = 64 / tl;
+  }
+  o.Kg = d.K * o.TL;
+  o.Tg = (o.T + o.TL - 1) / o.TL;
   o.Cp = (d.C + 63) / 64 * 64;
-  o.Kp = (d.K + 15) / 16 * 16;
-  o.Tp = (o.T + 15) / 16 * 16;
+  o.Kp = (o.Kg + 15) / 16 * 16;
+  o.Tp = (o.Tg + 15) / 16 * 16;
   o.P2 = t * t;
   o.Q = (o.P2 + 3) / 4;
   o.CB1 = (o.P2 + 15) / 16;

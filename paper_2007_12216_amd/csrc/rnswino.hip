@@ -32,6 +32,7 @@ KParams make_params(const rnswino_plan_t *pl) {
   const Dims &d = pl->dims;
   P.N = d.N; P.C = d.C; P.K = d.K; P.H = d.H; P.W = d.W; P.r = d.r; P.m = d.m; P.t = d.t; P.pad = d.pad;
   P.Ho = d.Ho; P.Wo = d.Wo; P.th = d.th; P.tw = d.tw; P.T = d.T; P.n = d.n;
+  P.TL = d.TL; P.Cq = d.Cq; P.Kg = d.Kg; P.Tg = d.Tg;
   P.Cp = d.Cp; P.Kp = d.Kp; P.Tp = d.Tp; P.P2 = d.P2; P.Q = d.Q;
   P.CB1 = d.CB1; P.KS1 = d.KS1; P.RB3 = d.RB3; P.KS3 = d.KS3;
   P.crt24 = 1;
@@ -86,16 +87,25 @@ inline void launch(Kern kern, dim3 grid, hipStream_t st, Timing tm, Args... args
 template <bool WIDE>
 void launch_k1(const rnswino_plan_t *plan, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
   const Dims &d = plan->dims;
-  const long long units = (long long)d.T * (d.Cp / 64);
+  const long long units = (long long)d.Tg * (d.Cp / 64);
   // x: multiple of 8 (see xcd_chunked()); y: one block per residue, or one block for all residues when there are
   // enough units to fill the chip (the pixel gather is then done once instead of n times; measured on the VGG16
   // stack, two blocks per CU are already enough for that to win)
   const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)(units >= 512 ? 1 : d.n));
+  if (d.TL > 1) {
+    switch (d.KS1) {
+      case 1: launch(k1_input_transform<1, WIDE, true>, grid, st, tm, P, x, V); break;
+      case 2: launch(k1_input_transform<2, WIDE, true>, grid, st, tm, P, x, V); break;
+      case 3: launch(k1_input_transform<3, WIDE, true>, grid, st, tm, P, x, V); break;
+      default: launch(k1_input_transform<4, WIDE, true>, grid, st, tm, P, x, V); break;
+    }
+    return;
+  }
   switch (d.KS1) {
-    case 1: launch(k1_input_transform<1, WIDE>, grid, st, tm, P, x, V); break;
-    case 2: launch(k1_input_transform<2, WIDE>, grid, st, tm, P, x, V); break;
-    case 3: launch(k1_input_transform<3, WIDE>, grid, st, tm, P, x, V); break;
-    default: launch(k1_input_transform<4, WIDE>, grid, st, tm, P, x, V); break;
+    case 1: launch(k1_input_transform<1, WIDE, false>, grid, st, tm, P, x, V); break;
+    case 2: launch(k1_input_transform<2, WIDE, false>, grid, st, tm, P, x, V); break;
+    case 3: launch(k1_input_transform<3, WIDE, false>, grid, st, tm, P, x, V); break;
+    default: launch(k1_input_transform<4, WIDE, false>, grid, st, tm, P, x, V); break;
   }
 }
 
@@ -147,7 +157,7 @@ void launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V
 // ---- K3 ----
 template <int NRES, bool WIDE>
 void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
-  const long long units = ((long long)d.K * d.T + 15) / 16;
+  const long long units = ((long long)d.Kg * d.Tg + 15) / 16;
   const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)((d.RB3 + 3) / 4));   // x multiple of 8: see xcd_chunked()
   switch (d.KS3) {
     case 1: launch(k3_inverse_crt<NRES, 1, WIDE>, grid, st, tm, P, O, y); break;
@@ -160,7 +170,7 @@ void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t 
 // streaming variant: 8-bit moduli, table of all residues at most 64 KiB, n * KS3 <= 8 (O operand in registers twice)
 template <int NRES, int KS3>
 void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
-  const long long blocks = ((long long)d.K * (d.Tp / 16) + 3) / 4;
+  const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
   const dim3 grid((unsigned)(blocks < max_blocks ? blocks : max_blocks));
   const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
   if (tm.start || tm.stop)
@@ -171,7 +181,7 @@ void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, in
 
 inline bool k3_stream_applies(const Dims &d) {
   return !d.wide && d.n * d.KS3 <= 8 && d.n <= 4 && d.KS3 <= 2 && (size_t)d.n * d.RB3 * d.KS3 * 1024 <= 65536 &&
-         (long long)d.K * (d.Tp / 16) >= 12LL * K3_STREAM_BLOCKS;   // three or more units per wave (measured on the VGG16 stack)
+         (long long)d.Kg * (d.Tp / 16) >= 12LL * K3_STREAM_BLOCKS;   // three or more units per wave (measured on the VGG16 stack)
 }
 
 void launch_k3_stream(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
@@ -411,23 +421,30 @@ int rnswino_debug_stage(const rnswino_plan_t *plan, int stage, const void *src_d
         return d.wide ? sym_residue(256 * (int64_t)raw[hi] + (int64_t)raw[lo], p) : sym_residue((int64_t)raw[narrow], p);
       };
       if (stage == RNSWINO_STAGE_U) {
+        // packed layers: the filter sits in every diagonal block (k * TL + tl, tl * Cq + c); block tl = 0 is read
         for (int k = 0; k < d.K; ++k)
-          for (int c = 0; c < d.C; ++c)
+          for (int c = 0; c < d.C; ++c) {
+            const int kg = k * d.TL;
             host_out[((size_t)slab * d.K + k) * d.C + c] =
-                d.wide ? value(0, u_offset_wide(slab, k, c, d.Kp, d.Cp, 0), u_offset_wide(slab, k, c, d.Kp, d.Cp, 1))
-                       : value(u_offset(slab, k, c, d.Kp, d.Cp), 0, 0);
+                d.wide ? value(0, u_offset_wide(slab, kg, c, d.Kp, d.Cp, 0), u_offset_wide(slab, kg, c, d.Kp, d.Cp, 1))
+                       : value(u_offset(slab, kg, c, d.Kp, d.Cp), 0, 0);
+          }
       } else if (stage == RNSWINO_STAGE_V) {
         for (int tau = 0; tau < d.T; ++tau)
-          for (int c = 0; c < d.C; ++c)
+          for (int c = 0; c < d.C; ++c) {
+            const int tg = tau % d.Tg, cg = (tau / d.Tg) * d.Cq + c;       // GEMM column and channel (cg = c when TL = 1)
             host_out[((size_t)slab * d.T + tau) * d.C + c] =
-                d.wide ? value(0, v_offset_wide(slab, d.n * d.P2, tau, c, d.Cp, 0), v_offset_wide(slab, d.n * d.P2, tau, c, d.Cp, 1))
-                       : value(v_offset(slab, d.n * d.P2, tau, c, d.Cp), 0, 0);
+                d.wide ? value(0, v_offset_wide(slab, d.n * d.P2, tg, cg, d.Cp, 0), v_offset_wide(slab, d.n * d.P2, tg, cg, d.Cp, 1))
+                       : value(v_offset(slab, d.n * d.P2, tg, cg, d.Cp), 0, 0);
+          }
       } else {
         for (int k = 0; k < d.K; ++k)
-          for (int tau = 0; tau < d.T; ++tau)
+          for (int tau = 0; tau < d.T; ++tau) {
+            const int kg = k * d.TL + tau / d.Tg, tg = tau % d.Tg;          // GEMM row and column
             host_out[((size_t)slab * d.K + k) * d.T + tau] =
-                d.wide ? value(0, o_offset_wide(i, pt, k, tau, d.n, d.Q, d.Kp, d.Tp, 0), o_offset_wide(i, pt, k, tau, d.n, d.Q, d.Kp, d.Tp, 1))
-                       : value(o_offset(i, pt, k, tau, d.n, d.Q, d.Kp, d.Tp), 0, 0);
+                d.wide ? value(0, o_offset_wide(i, pt, kg, tg, d.n, d.Q, d.Kp, d.Tp, 0), o_offset_wide(i, pt, kg, tg, d.n, d.Q, d.Kp, d.Tp, 1))
+                       : value(o_offset(i, pt, kg, tg, d.n, d.Q, d.Kp, d.Tp), 0, 0);
+          }
       }
     }
   }

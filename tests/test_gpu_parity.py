@@ -35,6 +35,10 @@ STAGE_CASES = [
     (1, 7, 3, 28, 14, 3, 14, 1, (65521, 65519)),             # 16-bit moduli
     (1, 4, 4, 12, 12, 3, 10, 1, (253, 251, 247)),            # the paper's running example (composite moduli)
     (1, 4, 4, 10, 10, 3, 8, 0, (251, 241, 239)),             # no padding
+    (4, 3, 5, 61, 64, 3, 8, 1, (251, 241, 239)),             # 3 channels: 16 tiles share a 64-channel block (ragged last group)
+    (2, 7, 6, 40, 44, 3, 8, 1, (251, 241, 239)),             # 7 channels: 8 tiles per block
+    (1, 12, 9, 60, 52, 3, 6, 1, (251, 241, 239)),            # 12 channels: 4 tiles per block
+    (1, 20, 18, 40, 24, 3, 4, 1, (65521, 65519)),            # 20 channels: 2 tiles per block, 16-bit moduli
 ]
 
 
@@ -259,6 +263,9 @@ NETWORK_CASES = [
     # synthetic stand-ins with the shapes of other networks' stride-1 layers (the paper's Tables 4 and 5 name ResNet50's
     # 3x3 layers and Inception-v3's 5x5 layer); seeded uniform int8 values, batch 2
     # name, N, C, K, H, W, r, m, pad, moduli
+    ("first layer 3x3 3->64 224x224", 1, 3, 64, 224, 224, 3, 8, 1, (251, 241, 239)),
+    ("first layer 3x3 3->32 96x96, F(4,3)", 2, 3, 32, 96, 96, 3, 4, 1, (251, 241, 239)),
+    ("5x5 16->32 48x48, F(12,5)", 2, 16, 32, 48, 48, 5, 12, 2, (251, 241, 239, 233)),
     ("resnet 3x3 64->64 56x56", 2, 64, 64, 56, 56, 3, 8, 1, (251, 241, 239, 233)),
     ("resnet 3x3 128->128 28x28", 2, 128, 128, 28, 28, 3, 8, 1, (251, 241, 239, 233)),
     ("resnet 3x3 256->256 14x14", 2, 256, 256, 14, 14, 3, 8, 1, (251, 241, 239, 233)),
