@@ -131,11 +131,12 @@ void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_
 template <int NTB, bool WIDE>
 void launch_k2_ntb(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
   const int ncb = d.Cp / 64;
-  // 64 rows per wave when K is large (V re-reads dominate) and that still leaves >= 4 blocks per CU; measured on the
+  // 64 rows per wave when K is large (V re-reads dominate), the contraction has more than one step and that still
+  // leaves >= 4 blocks per CU; measured on the
   // VGG16 stack this wins for K >= 256 and loses for K <= 128 (8-bit moduli, full-width tiles only: the register
   // budget of the other variants is spent on their extra accumulators)
   const long long big_blocks = (long long)((d.n * d.Q + 7) / 8 * 8) * ((d.Kp + 63) / 64) * ((d.Tp / 16 + NTB - 1) / NTB);
-  if (!WIDE && NTB == 4 && d.Kp >= 256 && big_blocks >= 1024) {
+  if (!WIDE && NTB == 4 && d.Kp >= 256 && ncb >= 2 && big_blocks >= 1024) {
     if (ncb % 2 == 0) launch_k2_one<2, NTB, (WIDE || NTB != 4) ? 2 : 4, WIDE>(d, P, U, V, O, st, tm);
     else launch_k2_one<1, NTB, (WIDE || NTB != 4) ? 2 : 4, WIDE>(d, P, U, V, O, st, tm);
     return;
