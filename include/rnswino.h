@@ -152,10 +152,10 @@ int rnswino_plan_get_matrix(const rnswino_plan_t *plan, int which, int modulus_i
 
 /* Copy the Kronecker table of one modulus, as the kernels read it, to host_out: which = RNSWINO_TABLE_INPUT is
  * (B^T kron B^T) mod p (input transform, section 5: V = B^T d B) as int8 [CB][KS1][planes][64 lanes][16]: fragment (cb, s)
- * holds, for lane l and byte b, the entry of transform point 16 cb + l%16 and tile pixel (row 4 s + l/16, column b), zero
- * outside the t x t tile; which = RNSWINO_TABLE_INVERSE is (A^T kron A^T) (P/p)^-1 mod p (inverse transform folded with
+ * holds, for lane l and byte b, the entry of transform point 16 cb + l%16 and contraction slot f = 64 s + 16 (l/16) + b =
+ * tile pixel (row f / RP, column f % RP), RP = 4 ceil(t/4), zero outside the t x t tile; which = RNSWINO_TABLE_INVERSE is (A^T kron A^T) (P/p)^-1 mod p (inverse transform folded with
  * the CRT factor, sections 3 and 5) as int8 [RB][KS3][planes][64][16]: fragment (rb, s), lane l, byte b = output
- * 16 rb + l%16 and transform point 64 s + 16 (l/16) + b.  CB = ceil(t^2/16), KS1 = ceil(t/4), RB = ceil(m^2/16),
+ * 16 rb + l%16 and transform point 64 s + 16 (l/16) + b.  CB = ceil(t^2/16), KS1 = ceil(t RP / 64), RB = ceil(m^2/16),
  * KS3 = ceil(t^2/64); planes = 1 (8-bit moduli: the symmetric residue) or 2 (16-bit moduli: high byte plane, then low
  * byte plane, entry = 256 h + l).  Returns the number of bytes (copied only if capacity suffices), or a negative code. */
 #define RNSWINO_TABLE_INPUT 0

@@ -4,12 +4,13 @@
 // by all K filters).  B^T d B = (B^T kron B^T) vec(d): per residue one dense (t*t) x (t*t) matrix applied to the
 // t*t pixels of a tile, i.e. a GEMM whose columns are the (tile, channel) pairs.  MFMA roles
 // (v_mfma_i32_16x16x64_i8): A operand = pixels (rows = 16 channels of one tile), B operand = the Kronecker
-// table (columns = 16 transform points), contraction index = pixel.  A contraction step of 64 covers four tile
-// rows of 16 pixels each (lane group g = row 4s+g; columns >= t have weight 0), so a lane's 16 operand bytes are
-// 16 consecutive pixels of one image row: one unaligned 16-byte load, masked where the tile hangs over the
-// image border (zero padding and ragged last tiles).
+// table (columns = 16 transform points), contraction index = pixel.  A tile row takes RP1 = 4 ceil(t/4)
+// contraction slots (its t pixels, then zero weights), the tile t * RP1 slots in KS1 = ceil(t * RP1 / 64) steps of
+// 64 (t = 10: 120 slots, two steps; rows of 16 slots would need three).  A row segment is one unaligned 16-byte
+// load of an image row, masked where the tile hangs over the image border (zero padding and ragged last tiles),
+// of which the first RP1 bytes go to LDS; a lane's 16 operand bytes are then 16 consecutive slots.
 //
-// Block = (tile, block of 64 channels, one residue or all of them): its 64 x t x 16 pixel patch is gathered once into
+// Block = (tile, block of 64 channels, one residue or all of them): its 64 x t x RP1 pixel patch is gathered once into
 // LDS (the gather of 16-byte row segments is what costs; sharing it between the four waves pays), then each wave
 // walks over its steps (residue, every fourth group of K1_CPW column blocks), the table fragments of the next
 // step in flight while the current one is multiplied.  Accumulator rows are channels 4g+j, so the four channel
@@ -29,10 +30,10 @@ constexpr int K1_CPW = 2;
 template <int KS1, bool WIDE, bool PACK>
 __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_t *__restrict__ x,
                                                            int8_t *__restrict__ V) {
-  constexpr int ROWS = 4 * KS1;
+  constexpr int ROWS = KS1 == 1 ? 8 : KS1 == 2 ? 10 : KS1 == 3 ? 12 : 16;   // largest t with this many steps
   constexpr int PL = WIDE ? 2 : 1;
-  constexpr int CROW = (ROWS + 1) * 16;   // bytes per channel in LDS: one 16-byte pad, so that the 16 channels a
-                                          // fragment read touches fall into different banks
+  constexpr int CROW = (4 * KS1 + 1) * 16;   // bytes per channel in LDS: one 16-byte pad, so that the 16 channels a
+                                             // fragment read touches fall into different banks
   __shared__ __attribute__((aligned(16))) uint8_t xs[64 * CROW];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: table addresses stay scalar
   const int lane = threadIdx.x & 63, g = lane >> 4;
@@ -118,7 +119,15 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
       uint32_t cmask[4];
       column_mask(sx0[k], cmask);
       val[k][0] &= cmask[0]; val[k][1] &= cmask[1]; val[k][2] &= cmask[2]; val[k][3] &= cmask[3];
-      if (task < 64 * ROWS) *(v4i *)(xs + c * CROW + a * 16) = val[k];
+      // the first RP1 bytes of the segment are the row's slots (the slots past t * RP1 are never written: their
+      // table entries are zero, and any byte times zero is zero)
+      if (task < 64 * ROWS && a < P.t) {
+        uint32_t *row = (uint32_t *)(xs + c * CROW + a * P.RP1);
+        row[0] = (uint32_t)val[k][0];
+        if (P.RP1 > 4) row[1] = (uint32_t)val[k][1];
+        if (P.RP1 > 8) row[2] = (uint32_t)val[k][2];
+        if (P.RP1 > 12) row[3] = (uint32_t)val[k][3];
+      }
     }
   }
   // This wave's work: steps (residue i, column-block group cg) with cg = wave, wave + 4, ...  The table fragments
@@ -152,7 +161,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
 #pragma unroll
   for (int u = 0; u < 4; ++u)
 #pragma unroll
-    for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + (16 * u + (lane & 15)) * CROW + (4 * s + g) * 16);
+    for (int s = 0; s < KS1; ++s) af[u][s] = *(const v4i *)(xs + (16 * u + (lane & 15)) * CROW + (4 * s + g) * 16);   // slots 64 s + 16 g ..
 
   // One step with the fragments in `b`, while those of the following step travel into `bnext`.  The loop below
   // alternates the two register sets instead of copying one into the other: a copy would have to wait for every

@@ -21,7 +21,7 @@ struct KParams {
   double inv_pd[8];           // 1 / p_i
   const int32_t *G;           // device table [n][t*r] for the filter transform
   // transforms on the matrix cores: Kronecker tables in operand-fragment order (see plan_math.cpp)
-  int CB1, KS1, RB3, KS3;
+  int CB1, KS1, RP1, RB3, KS3;
   const int8_t *KB;           // (B^T kron B^T) mod p          [n][CB1][KS1][planes][64 lanes][16]
   const int8_t *KA;           // (A^T kron A^T) crt_inv mod p  [n][RB3][KS3][planes][64 lanes][16]
   uint32_t crt_c[8];          // prod_{l != i} p_l mod 2^32

@@ -21,7 +21,8 @@ struct Dims {
   int Cp, Kp, Tp;            // GEMM extents of the tiled tensors: channels padded to 64, Kg and Tg padded to 16
   int P2;                    // t*t transform points
   int Q;                     // ceil(t*t / 4): groups of four transform points in the O tensor
-  int CB1, KS1;              // input transform on MFMA: 16-point column blocks ceil(t*t/16), contraction steps ceil(t/4)
+  int CB1, KS1, RP1;         // input transform on MFMA: 16-point column blocks ceil(t*t/16); a tile row takes RP1 = 4 ceil(t/4)
+                             // contraction slots (its t pixels, then zeros), the tile t * RP1: KS1 = ceil(t * RP1 / 64) steps
   int RB3, KS3;              // inverse transform on MFMA: 16-output row blocks ceil(m*m/16), contraction steps ceil(t*t/64)
 };
 

@@ -183,7 +183,8 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
   o.P2 = t * t;
   o.Q = (o.P2 + 3) / 4;
   o.CB1 = (o.P2 + 15) / 16;
-  o.KS1 = (t + 3) / 4;
+  o.RP1 = (t + 3) / 4 * 4;
+  o.KS1 = (t * o.RP1 + 63) / 64;
   o.RB3 = (d.m * d.m + 15) / 16;
   o.KS3 = (o.P2 + 63) / 64;
   // the kernels address the GEMM output O = [Kp][n][Q][Tp] words (two planes for 16-bit moduli) with 32-bit byte
@@ -203,7 +204,8 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
 // fragment order of v_mfma_i32_16x16x64_i8: a fragment is 16 rows (or columns) x 64 contraction elements,
 // lane l holds row l%16 and the 16 contraction elements of slice g = l/16.
 //   KB (input transform, B operand): fragment (cbk, s): column = transform point 16*cbk + l%16,
-//       contraction element (g, b) = pixel (row 4s+g, column b) of the tile; zero for b >= t or row >= t.
+//       contraction element (g, b) = slot f = 64s + 16g + b = pixel (row f / RP1, column f % RP1) of the tile, where a
+//       tile row takes RP1 = 4 ceil(t/4) slots; zero for column >= t or row >= t.
 //   KA (inverse transform, A operand): fragment (rb, s): row = output u*m+v = 16*rb + l%16,
 //       contraction element (g, b) = transform point 64s + 16g + b.  Each entry is multiplied by
 //       (P/p_i)^-1 mod p_i so that the kernel's accumulator is directly the CRT coefficient of the residue.
@@ -264,10 +266,11 @@ void build_tables(rnswino_plan_s &pl, std::vector<char> &blob) {
       for (int s = 0; s < d.KS1; ++s)
         for (int lane = 0; lane < 64; ++lane)
           for (int b = 0; b < 16; ++b) {
-            const int pt = 16 * cbk + (lane & 15), a = 4 * s + (lane >> 4);
+            const int pt = 16 * cbk + (lane & 15), slot = 64 * s + 16 * (lane >> 4) + b;
+            const int a = slot / d.RP1, col = slot % d.RP1;
             int32_t v = 0;
-            if (pt < d.P2 && a < d.t && b < d.t)
-              v = sym_residue((int64_t)BT[(size_t)(pt / d.t) * d.t + a] * BT[(size_t)(pt % d.t) * d.t + b], p);
+            if (pt < d.P2 && a < d.t && col < d.t)
+              v = sym_residue((int64_t)BT[(size_t)(pt / d.t) * d.t + a] * BT[(size_t)(pt % d.t) * d.t + col], p);
             put_entry(kb + (size_t)(cbk * d.KS1 + s) * planes * 1024, planes, lane, b, v, p);
           }
     int8_t *ka = (int8_t *)blob.data() + pl.off_KA + (size_t)i * d.RB3 * d.KS3 * planes * 1024;

@@ -34,7 +34,7 @@ KParams make_params(const rnswino_plan_t *pl) {
   P.Ho = d.Ho; P.Wo = d.Wo; P.th = d.th; P.tw = d.tw; P.T = d.T; P.n = d.n;
   P.TL = d.TL; P.Cq = d.Cq; P.Kg = d.Kg; P.Tg = d.Tg;
   P.Cp = d.Cp; P.Kp = d.Kp; P.Tp = d.Tp; P.P2 = d.P2; P.Q = d.Q;
-  P.CB1 = d.CB1; P.KS1 = d.KS1; P.RB3 = d.RB3; P.KS3 = d.KS3;
+  P.CB1 = d.CB1; P.KS1 = d.KS1; P.RP1 = d.RP1; P.RB3 = d.RB3; P.KS3 = d.KS3;
   P.crt24 = 1;
   for (int i = 0; i < d.n; ++i) {
     P.p[i] = (int)pl->desc.moduli[i];

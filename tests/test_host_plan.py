@@ -161,16 +161,19 @@ def test_kronecker_tables_against_the_oracle_matrices(m, r, moduli):
             return 256 * int(frags[base, lane, b]) + int(frags[base + 1, lane, b])
 
         kb = rn.rnswino_plan_get_table(plan, rn.TABLE_INPUT, i)
-        ks1, cb1 = (t + 3) // 4, (t * t + 15) // 16
+        rp = (t + 3) // 4 * 4                               # contraction slots per tile row
+        ks1, cb1 = (t * rp + 63) // 64, (t * t + 15) // 16
         assert kb.shape[0] == cb1 * ks1 * planes
         for cb in range(cb1):
             for s in range(ks1):
                 for lane in range(64):
-                    pt, a = 16 * cb + lane % 16, 4 * s + lane // 16
+                    pt = 16 * cb + lane % 16
                     for b in range(16):
+                        slot = 64 * s + 16 * (lane // 16) + b
+                        a, col = slot // rp, slot % rp
                         got = entry(kb, cb, s, lane, b, ks1)
-                        if pt < t * t and a < t and b < t:
-                            assert (got - int(BT[pt // t][a]) * int(BT[pt % t][b])) % p == 0 and abs(got) <= (p - 1) // 2 + (130 if planes == 2 else 0)
+                        if pt < t * t and a < t and col < t:
+                            assert (got - int(BT[pt // t][a]) * int(BT[pt % t][col])) % p == 0 and abs(got) <= (p - 1) // 2 + (130 if planes == 2 else 0)
                         else:
                             assert got == 0
         ka = rn.rnswino_plan_get_table(plan, rn.TABLE_INVERSE, i)
