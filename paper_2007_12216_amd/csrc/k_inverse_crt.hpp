@@ -15,6 +15,15 @@
 // every moduli set whose product can matter for a 32-bit result), or in binary32 when the layer's worst case
 // 2^14 r^2 C keeps |y/P| below 0.45 (the host decides: KParams::quot32).
 //
+// Fast conversion (8-bit moduli, KParams::fastcrt): the accumulator a_i is not reduced at all.  a_i is congruent to
+// w_i modulo p_i, and (P/p_i) p_i = P, so S = sum_i (P/p_i) a_i is congruent to y modulo P and y = S - P rint(S/P) with
+// S/P = sum_i a_i / p_i.  The accumulators start at 2^22 (|a_i| <= t*t * 126 * 128 <= 2^22), so that a_i + 2^22 is an
+// unsigned 23-bit number: one 24-bit multiply-add (P/p_i < 2^24) and one binary32 multiply-add per residue and
+// output; the constants that undo the offset sit in KParams (crt_sum0, crt_fs0).  The binary32 sum carries an
+// error of a few hundredths (bounded on the host from the moduli), so the host enables this path only when the
+// layer's worst case keeps |y/P| that far below 1/2 -- true for every layer whose moduli were chosen by the
+// range bound with a little room, e.g. all five benchmark workloads.
+//
 // Block = one unit of 16 consecutive (k, tile) pairs and four 16-output row blocks rb = 4*blockIdx.y + wave; every
 // wave loads the O operand itself (the copies hit in L1): a wave-uniform row of O plus a 32-bit lane offset per
 // word.  No LDS.
@@ -80,11 +89,30 @@ __device__ __forceinline__ void crt_convert(const KParams &P, const uint32_t (&w
   }
 }
 
+// Fast conversion (see the header): w[i][j] = a_i + 2^22, unreduced.
 template <int NRES>
+__device__ __forceinline__ void crt_convert_fast(const KParams &P, const uint32_t (&w)[NRES][4], int (&val)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t sum = P.crt_sum0;
+    float fs = P.crt_fs0;
+#pragma unroll
+    for (int i = 0; i < NRES; ++i) {
+      sum += __umul24(P.crt_c[i], w[i][j]);
+      fs = __builtin_fmaf((float)w[i][j], P.inv_p[i], fs);
+    }
+    const int kk = (int)__builtin_rintf(fs);
+    val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+  }
+}
+
+template <int NRES, bool FAST>
 __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uint32_t (&w)[NRES][4], int rb, int g,
                                                      const TilePos &tp, int32_t *__restrict__ y) {
   int val[4];
-  if (P.crt24) {                      // uniform: one branch per call instead of one per multiply
+  if (FAST) {
+    crt_convert_fast<NRES>(P, w, val);
+  } else if (P.crt24) {               // uniform: one branch per call instead of one per multiply
     if (P.quot32) crt_convert<NRES, true, true>(P, w, val);
     else crt_convert<NRES, true, false>(P, w, val);
   } else {
@@ -139,7 +167,8 @@ __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uin
   }
 }
 
-template <int NRES, int KS3, bool WIDE>
+// FAST: the conversion with unreduced accumulators (the host launches it when KParams::fastcrt is set).
+template <int NRES, int KS3, bool WIDE, bool FAST>
 __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t *__restrict__ O,
                                                        int32_t *__restrict__ y) {
   constexpr int PL = WIDE ? 2 : 1;
@@ -196,7 +225,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
     for (int i = 0; i < NRES; ++i) {
       v4i acc[NACC];
 #pragma unroll
-      for (int a = 0; a < NACC; ++a) acc[a] = (v4i){0, 0, 0, 0};
+      for (int a = 0; a < NACC; ++a) acc[a] = FAST ? (v4i){P.acc0, P.acc0, P.acc0, P.acc0} : (v4i){0, 0, 0, 0};
       const int8_t *ka = P.KA + (((size_t)i * P.RB3 + rb) * KS3) * (1024 * PL) + lane * 16;
 #pragma unroll
       for (int s = 0; s < KS3; ++s) {
@@ -219,12 +248,12 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
           const long long tot = (long long)acc[0][j] * 65536 + (long long)acc[1][j] * 256 + (long long)acc[NACC - 1][j];
           w[i][j] = (uint32_t)(mod_near64(tot, P.inv_pd[i], P.p[i]) + P.p[i]);
         } else {
-          // |acc| <= t*t * 126 * 127 < 2^24
-          w[i][j] = mod_near_plus_p(acc[0][j], P.inv_p[i], -P.p[i], P.bias_p[i]);
+          // |acc| <= t*t * 126 * 128 <= 2^22 (plus the 2^22 of the fast conversion, which then takes it as it is)
+          w[i][j] = FAST ? (uint32_t)acc[0][j] : mod_near_plus_p(acc[0][j], P.inv_p[i], -P.p[i], P.bias_p[i]);
         }
       }
     }
-    k3_convert_and_store<NRES>(P, w, rb, g, tile_position(P, k, tau), y);
+    k3_convert_and_store<NRES, FAST>(P, w, rb, g, tile_position(P, k, tau), y);
   }
 }
 
@@ -235,7 +264,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
 // Grid: min(ceil(units / 4), three blocks per CU) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
 constexpr int K3_STREAM_BLOCKS = 768;   // three resident blocks per CU (register budget) on 256 CUs
 
-template <int NRES, int KS3>
+template <int NRES, int KS3, bool FAST>
 __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const uint32_t *__restrict__ O,
                                                               int32_t *__restrict__ y) {
   extern __shared__ __attribute__((aligned(16))) uint8_t ka_lds[];
@@ -275,6 +304,8 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
 
   // One unit with its O operand in `o`, while the operand of the wave's next unit travels into `onext`; the loop
   // alternates the two register sets (a copy would wait for every memory operation issued before it).
+  const int a0 = FAST ? P.acc0 : 0;                 // 2^22 for the fast conversion
+  const v4i acc_start = (v4i){a0, a0, a0, a0};
   auto do_unit = [&](int u, v4i (&o)[NRES][KS3], v4i (&onext)[NRES][KS3]) {
     if (u + nwaves < nunits) load_o(u + nwaves, onext);
     const int kg = u / ntb, taug = (u - kg * ntb) * 16 + (lane & 15);
@@ -284,17 +315,19 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
       uint32_t w[NRES][4];
 #pragma unroll
       for (int i = 0; i < NRES; ++i) {
-        v4i acc = (v4i){0, 0, 0, 0};
+        v4i acc = acc_start;
 #pragma unroll
         for (int s = 0; s < KS3; ++s) {
           const v4i a = *(const v4i *)(ka_lds + (((i * P.RB3 + rb) * KS3) + s) * 1024 + lane * 16);
           acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, o[i][s], acc, 0, 0, 0);
         }
-        // |acc| <= t*t * 126 * 127 < 2^24; residue shifted by +p so that it is non-negative
+        // |acc| <= t*t * 126 * 128 <= 2^22: the fast conversion takes acc + 2^22 as it is, the general one the
+        // residue shifted by +p so that it is non-negative
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[i][j] = mod_near_plus_p(acc[j], P.inv_p[i], -P.p[i], P.bias_p[i]);
+        for (int j = 0; j < 4; ++j)
+          w[i][j] = FAST ? (uint32_t)acc[j] : mod_near_plus_p(acc[j], P.inv_p[i], -P.p[i], P.bias_p[i]);
       }
-      k3_convert_and_store<NRES>(P, w, rb, g, tp, y);
+      k3_convert_and_store<NRES, FAST>(P, w, rb, g, tp, y);
     }
   };
   v4i oa[NRES][KS3], ob[NRES][KS3];

@@ -51,6 +51,24 @@ KParams make_params(const rnswino_plan_t *pl) {
     for (int i = 0; i < d.n; ++i) { prod *= pl->desc.moduli[i]; if (prod > cap) prod = cap; }
     const unsigned __int128 worst = (unsigned __int128)16384u * (unsigned)d.r * (unsigned)d.r * (unsigned)d.C;
     P.quot32 = (worst * 20 <= prod * 9) ? 1 : 0;
+    // Fast conversion: the binary32 sum of (a_i + 2^22) / p_i - B, B = 2^22 sum_i 1/p_i, stays within [-B, B]; it
+    // takes n + 1 roundings of at most half an ulp of 2B each, and the rounded 1/p_i add at most 2B 2^-23 in all.
+    // Enabled when the layer's worst case leaves twice that error below 0.49 - |y|/P.
+    if (!d.wide && P.crt24 && prod < cap) {
+      double B = 0.0;
+      uint32_t c32 = 0;
+      for (int i = 0; i < d.n; ++i) { B += 4194304.0 / (double)pl->desc.moduli[i]; c32 += pl->crt_c[i]; }
+      int e = 0;
+      std::frexp(2.0 * B, &e);                                   // 2B = f * 2^e, f in [0.5, 1)
+      const double half_ulp = std::ldexp(1.0, e - 24 - 1);      // binary32: ulp = 2^(e - 24)
+      const double err = (d.n + 1) * half_ulp + 2.0 * B * std::ldexp(1.0, -23);
+      if ((double)worst / (double)prod + 2.0 * err <= 0.49) {
+        P.fastcrt = 1;
+        P.acc0 = 4194304;
+        P.crt_sum0 = 0u - 4194304u * c32;
+        P.crt_fs0 = (float)(-B);
+      }
+    }
   }
   P.prod_mod32 = pl->prod_mod32;
   const char *base = (const char *)pl->d_tables;
@@ -160,11 +178,20 @@ template <int NRES, bool WIDE>
 void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
   const long long units = ((long long)d.Kg * d.Tg + 15) / 16;
   const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)((d.RB3 + 3) / 4));   // x multiple of 8: see xcd_chunked()
+  if (!WIDE && P.fastcrt) {
+    switch (d.KS3) {
+      case 1: launch(k3_inverse_crt<NRES, 1, false, true>, grid, st, tm, P, O, y); break;
+      case 2: launch(k3_inverse_crt<NRES, 2, false, true>, grid, st, tm, P, O, y); break;
+      case 3: launch(k3_inverse_crt<NRES, 3, false, true>, grid, st, tm, P, O, y); break;
+      default: launch(k3_inverse_crt<NRES, 4, false, true>, grid, st, tm, P, O, y); break;
+    }
+    return;
+  }
   switch (d.KS3) {
-    case 1: launch(k3_inverse_crt<NRES, 1, WIDE>, grid, st, tm, P, O, y); break;
-    case 2: launch(k3_inverse_crt<NRES, 2, WIDE>, grid, st, tm, P, O, y); break;
-    case 3: launch(k3_inverse_crt<NRES, 3, WIDE>, grid, st, tm, P, O, y); break;
-    default: launch(k3_inverse_crt<NRES, 4, WIDE>, grid, st, tm, P, O, y); break;
+    case 1: launch(k3_inverse_crt<NRES, 1, WIDE, false>, grid, st, tm, P, O, y); break;
+    case 2: launch(k3_inverse_crt<NRES, 2, WIDE, false>, grid, st, tm, P, O, y); break;
+    case 3: launch(k3_inverse_crt<NRES, 3, WIDE, false>, grid, st, tm, P, O, y); break;
+    default: launch(k3_inverse_crt<NRES, 4, WIDE, false>, grid, st, tm, P, O, y); break;
   }
 }
 
@@ -174,10 +201,11 @@ void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, in
   const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
   const dim3 grid((unsigned)(blocks < max_blocks ? blocks : max_blocks));
   const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
+  auto kern = P.fastcrt ? k3_inverse_crt_stream<NRES, KS3, true> : k3_inverse_crt_stream<NRES, KS3, false>;
   if (tm.start || tm.stop)
-    hipExtLaunchKernelGGL((k3_inverse_crt_stream<NRES, KS3>), grid, dim3(256), lds, st, tm.start, tm.stop, 0, P, O, y);
+    hipExtLaunchKernelGGL(kern, grid, dim3(256), lds, st, tm.start, tm.stop, 0, P, O, y);
   else
-    hipLaunchKernelGGL((k3_inverse_crt_stream<NRES, KS3>), grid, dim3(256), lds, st, P, O, y);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, P, O, y);
 }
 
 inline bool k3_stream_applies(const Dims &d) {
