@@ -149,6 +149,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
           b[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
         }
   };
+  const uint32_t lane_store = (uint32_t)(lane & 15) * (uint32_t)(ncb * PL * 1024) + g * 16;   // 16 points * ncb KiB: far below 2^32
   v4i bf[K1_CPW][KS1][PL], bn[K1_CPW][KS1][PL];
   if (nsteps > 0) load_table(0, bf);
   __syncthreads();
@@ -189,7 +190,10 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
           for (int u = 0; u < 4; ++u)
             acc[pl][u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b[cc][s][pl], acc[pl][u], 0, 0, 0);
       const int pt = 16 * cbk + (lane & 15);
-      int8_t *dst = V + ((((size_t)(tau >> 4) * (P.n * P.P2) + (i * P.P2 + pt)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64 + g * 16;
+      // wave-uniform 64-bit part (tile block, residue, column block, channel block, tile) + the lane's 32-bit part
+      // (its transform point within the column block, its four channels): the address costs the vector unit nothing
+      const size_t at = ((((size_t)(tau >> 4) * (P.n * P.P2) + (i * P.P2 + 16 * cbk)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64;
+      int8_t *dst = V + at + lane_store;
       if (WIDE) {
         // per plane |acc| <= t*t * 128 * 128 = 2^22, so 256 * acc_h + acc_l fits 32 bits
         v4i out_h, out_l;

@@ -125,24 +125,28 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
         for (int tb = 0; tb < NTB; ++tb) acc[a][rm][tb] = (v4i){0, 0, 0, 0};
   }
 
-  // the four results of a point group become the four bytes of one word, through LDS
-  uint8_t *tile8 = (uint8_t *)tile;
+  // the four results of a point group become the four bytes of one word, through LDS.  The lane's part of the
+  // address is computed once and hidden from the optimiser, so that each byte store carries its (compile-time)
+  // row and column as the instruction's immediate offset instead of recomputing the address.
+  uint32_t lane_byte = (uint32_t)((4 * (lane >> 4)) * PITCH + (lane & 15) * PL) * 4 + wave;
+  asm volatile("" : "+v"(lane_byte));
+  uint8_t *tile8 = (uint8_t *)tile + lane_byte;
 #pragma unroll
   for (int rm = 0; rm < RM; ++rm)
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int row = rm * 16 + 4 * (lane >> 4) + j, col = tb * 16 + (lane & 15);
+        const int at = ((rm * 16 + j) * PITCH + tb * 16 * PL) * 4;   // row rm*16 + 4*(lane>>4) + j, column tb*16 + lane%16
         if (WIDE) {
           const long long tot = (long long)acc[0][rm][tb][j] * 65536 + (long long)acc[1][rm][tb][j] * 256 +
                                 (long long)acc[NACC - 1][rm][tb][j];
           const int v = storable16(mod_near64(tot, P.inv_pd[i], p), p);
           const int lo = (int)(int8_t)(v & 0xFF), hi = (v - lo) >> 8;
-          tile8[(row * PITCH + col * PL) * 4 + wave] = (uint8_t)hi;
-          tile8[(row * PITCH + col * PL + PL - 1) * 4 + wave] = (uint8_t)lo;
+          tile8[at] = (uint8_t)hi;
+          tile8[at + (PL - 1) * 4] = (uint8_t)lo;
         } else {
-          tile8[(row * PITCH + col) * 4 + wave] = (uint8_t)mod_lowbyte(acc[0][rm][tb][j], inv, -p);
+          tile8[at] = (uint8_t)mod_lowbyte(acc[0][rm][tb][j], inv, -p);
         }
       }
   __syncthreads();
