@@ -9,7 +9,9 @@ operation count 2*N*K*C*Ho*Wo*r^2 divided by the time per step.
 
 Timed region: each step uses its own weight/input/workspace set out of a rotation larger than the on-chip
 caches (L2 + Infinity Cache), so every step streams its operands from HBM ("cold"), as a network running
-layer after layer would.  The same loop on one buffer set ("warm") is reported beside it.
+layer after layer would.  With --warm the same loop on one buffer set is timed as well and reported beside it
+(off by default, so that every launch of the default command is a cold one and a kernel trace of that command
+averages over the same launches as the durations reported here).
 
 One JSON line is printed: the contract fields plus
   roofline     -- the slowest of the three kernels: algorithmic bytes per launch / its average duration, measured
@@ -34,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
 # (profiles/conv2d_config2_hbm_traffic.md).  Counters cannot be read from inside this script, so the figures are
 # recorded here for the workload they were taken on; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {2: {"input_transform": 7.75e6, "residue_gemm": 39.38e6, "inverse_transform_mrc": 10.12e6}}
+MEASURED_TRAFFIC_BYTES = {2: {"input_transform": 7.58e6, "residue_gemm": 39.37e6, "inverse_transform_mrc": 10.11e6}}
 ROTATION_BYTES = 640 << 20      # operands cycled through in the cold loop (> 256 MB Infinity Cache + 32 MB L2)
 
 
@@ -141,6 +143,7 @@ def main():
     ap.add_argument("--workload", type=int, default=2, choices=(1, 2, 3, 4, 5),
                     help="single-layer workload 1-4 (default 2, the one the metric is quoted on), or 5: the 13-layer stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--warm", action="store_true", help="also time the loop on one operand set (cache-warm)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -197,7 +200,7 @@ def main():
         return (time.perf_counter() - t0) / K_steps
 
     sec_cold = timed(step_cold)
-    sec_warm = timed(step_warm)
+    sec_warm = timed(step_warm) if args.warm else None
 
     # ---- per-kernel durations: HIP events around each kernel, same cold rotation, same step count ----------
     evs = HipEvents()
@@ -280,7 +283,8 @@ def main():
                                f"moduli={list(cfg['moduli'])}",
                    "direct_conv_GOP": round(ops / 1e9, 4), "cache": f"cold (rotation of {n_sets} operand sets, "
                    f"{n_sets * set_bytes >> 20} MiB)",
-                   "warm_value_TOPS": round(ops / sec_warm / 1e12, 3), "warm_ms_per_step": round(sec_warm * 1e3, 5),
+                   "warm_value_TOPS": round(ops / sec_warm / 1e12, 3) if sec_warm else None,
+                   "warm_ms_per_step": round(sec_warm * 1e3, 5) if sec_warm else None,
                    "bit_exact_vs_oracle": bit_exact, "library_int8_gemm_context": lib_gemm},
         "roofline": roofline,
         "cpu_baseline": cpu,
