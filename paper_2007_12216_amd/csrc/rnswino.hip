@@ -210,7 +210,7 @@ void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, in
 
 inline bool k3_stream_applies(const Dims &d) {
   return !d.wide && d.n * d.KS3 <= 8 && d.n <= 4 && d.KS3 <= 2 && (size_t)d.n * d.RB3 * d.KS3 * 1024 <= 65536 &&
-         (long long)d.Kg * (d.Tp / 16) >= 12LL * K3_STREAM_BLOCKS;   // three or more units per wave (measured on the VGG16 stack)
+         (long long)d.Kg * (d.Tp / 16) >= 4LL * K3_STREAM_BLOCKS;   // a unit or more per wave of the full grid (measured on the VGG16 stack)
 }
 
 void launch_k3_stream(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
