@@ -132,26 +132,38 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   }
   // This wave's work: steps (residue i, column-block group cg) with cg = wave, wave + 4, ...  The table fragments
   // of step k+1 are requested before step k is multiplied; those of step 0 before the barrier, so that their
-  // latency overlaps the gather.
+  // latency overlaps the gather.  A step's position is kept as wave-uniform scalars and advanced incrementally
+  // (no divisions, and only a few scalar operations per column block: every instruction counts here).
   const int ncg = (P.CB1 + K1_CPW - 1) / K1_CPW;
   const int per_i = (ncg - wave + 3) >> 2;            // groups of this wave per residue
   const int nsteps = (i1 - i0) * per_i;
-  auto load_table = [&](int step, v4i (&b)[K1_CPW][KS1][PL]) {
-    const int i = i0 + step / per_i, cg = wave + 4 * (step % per_i);
-    const int8_t *KBi = P.KB + (size_t)i * P.CB1 * KS1 * PL * 1024 + lane * 16;
+  struct Pos { int i, cg; };                          // residue and column-block group
+  auto advance = [&](Pos &q) {
+    q.cg += 4;
+    if (q.cg >= ncg) { q.cg = wave; ++q.i; }
+  };
+  constexpr uint32_t FRAG = KS1 * PL * 1024;          // table bytes per column block (all steps and planes)
+  const int8_t *KBl = P.KB + lane * 16;
+  auto load_table = [&](const Pos &q, v4i (&b)[K1_CPW][KS1][PL]) {
 #pragma unroll
-    for (int cc = 0; cc < K1_CPW; ++cc)
+    for (int cc = 0; cc < K1_CPW; ++cc) {
+      const int cbk = min(q.cg * K1_CPW + cc, P.CB1 - 1);
+      const int8_t *frag = KBl + (uint32_t)(q.i * P.CB1 + cbk) * FRAG;   // the whole table is far below 4 GiB
 #pragma unroll
       for (int s = 0; s < KS1; ++s)
 #pragma unroll
-        for (int pl = 0; pl < PL; ++pl) {
-          const int cbk = min(cg * K1_CPW + cc, P.CB1 - 1);
-          b[cc][s][pl] = *(const v4i *)(KBi + (((size_t)cbk * KS1 + s) * PL + pl) * 1024);
-        }
+        for (int pl = 0; pl < PL; ++pl) b[cc][s][pl] = *(const v4i *)(frag + (s * PL + pl) * 1024);
+    }
   };
-  const uint32_t lane_store = (uint32_t)(lane & 15) * (uint32_t)(ncb * PL * 1024) + g * 16;   // 16 points * ncb KiB: far below 2^32
+  // Where a column block's 16 transform points go in V: wave-uniform 64-bit part (tile block, residue, column block,
+  // channel block, tile) + the lane's 32-bit part (its point within the column block, its four channels), so the
+  // address costs the vector unit next to nothing.  stride_pt = bytes between consecutive transform points.
+  const uint32_t stride_pt = (uint32_t)(ncb * PL * 1024);
+  const uint32_t lane_store = (uint32_t)(lane & 15) * stride_pt + g * 16;   // 16 points * ncb KiB: far below 2^32
+  int8_t *const Vtile = V + ((size_t)(tau >> 4) * (size_t)(P.n * P.P2) * ncb + cb) * (PL * 1024) + (tau & 15) * 64;
   v4i bf[K1_CPW][KS1][PL], bn[K1_CPW][KS1][PL];
-  if (nsteps > 0) load_table(0, bf);
+  Pos cur = {i0, wave};
+  if (nsteps > 0) load_table(cur, bf);
   __syncthreads();
   if (nsteps <= 0) return;
   // All loads issued so far are awaited here, explicitly: otherwise the compiler, merging this entry state with the
@@ -168,8 +180,9 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
   // alternates the two register sets instead of copying one into the other: a copy would have to wait for every
   // memory operation issued before it, the step's own stores included.
   auto do_step = [&](int step, v4i (&b)[K1_CPW][KS1][PL], v4i (&bnext)[K1_CPW][KS1][PL]) {
-    if (step + 1 < nsteps) load_table(step + 1, bnext);
-    const int i = i0 + step / per_i, cg = wave + 4 * (step % per_i);
+    const int i = cur.i, cg = cur.cg;
+    advance(cur);
+    if (step + 1 < nsteps) load_table(cur, bnext);
     const int p = P.p[i];
     const float inv = P.inv_p[i];
     const double invd = P.inv_pd[i];
@@ -190,10 +203,7 @@ __global__ __launch_bounds__(256) void k1_input_transform(KParams P, const int8_
           for (int u = 0; u < 4; ++u)
             acc[pl][u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[u][s], b[cc][s][pl], acc[pl][u], 0, 0, 0);
       const int pt = 16 * cbk + (lane & 15);
-      // wave-uniform 64-bit part (tile block, residue, column block, channel block, tile) + the lane's 32-bit part
-      // (its transform point within the column block, its four channels): the address costs the vector unit nothing
-      const size_t at = ((((size_t)(tau >> 4) * (P.n * P.P2) + (i * P.P2 + 16 * cbk)) * ncb + cb) * PL) * 1024 + (tau & 15) * 64;
-      int8_t *dst = V + at + lane_store;
+      int8_t *dst = Vtile + (size_t)(uint32_t)(i * P.P2 + 16 * cbk) * stride_pt + lane_store;
       if (WIDE) {
         // per plane |acc| <= t*t * 128 * 128 = 2^22, so 256 * acc_h + acc_l fits 32 bits
         v4i out_h, out_l;
