@@ -89,6 +89,24 @@ def stage_bytes(cfg, plan):
     return {"input_transform": xb + vb, "residue_gemm": ub + vb + ob, "inverse_transform_mrc": ob + yb}
 
 
+INT8_MFMA_PEAK_TOPS = 5000.0
+
+
+def stage_mfma_ops(cfg, plan):
+    """int8 operations the matrix cores execute per launch of each kernel (2 per multiply-add, padding included):
+    the GEMM over channels padded to 64, rows and tiles padded to 16; the two transforms as Kronecker products with the
+    contraction padded to whole 64-element steps and the outputs to whole 16-row blocks.  16-bit moduli: four byte-plane
+    products per multiply-add in the GEMM and in the inverse transform, two table planes in the input transform."""
+    n, t, m = len(cfg["moduli"]), plan.t, cfg["m"]
+    wide = max(cfg["moduli"]) >= 256
+    up = lambda v, q: -(-v // q) * q
+    Cp, Kp, Tp = up(cfg["C"], 64), up(cfg["K"], 16), up(plan.T, 16)
+    slots1 = up(t * up(t, 4), 64)
+    return {"input_transform": 2.0 * n * up(t * t, 16) * slots1 * plan.T * Cp * (2 if wide else 1),
+            "residue_gemm": 2.0 * n * t * t * Kp * Cp * Tp * (4 if wide else 1),
+            "inverse_transform_mrc": 2.0 * n * up(m * m, 16) * up(t * t, 64) * cfg["K"] * plan.T * (4 if wide else 1)}
+
+
 def bench_stack(args, dev):
     """Workload 5: one step = one pass of the 13-layer VGG16 conv stack at batch 8 (conv, shift/clamp, pool chain)."""
     import numpy as np
@@ -222,6 +240,7 @@ def main():
     evs.destroy_all()
 
     bytes_per = stage_bytes(cfg, plan)
+    mfma_ops = stage_mfma_ops(cfg, plan)
     dominant = max(names, key=lambda nm: stage_ms[nm])
     achieved = bytes_per[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -229,7 +248,10 @@ def main():
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant),
                 "algorithmic_bytes": bytes_per[dominant],
                 "stage_us": {nm: round(stage_ms[nm] * 1e3, 2) for nm in names},
-                "stage_GBps": {nm: round(bytes_per[nm] / (stage_ms[nm] * 1e-3) / 1e9, 1) for nm in names}}
+                "stage_GBps": {nm: round(bytes_per[nm] / (stage_ms[nm] * 1e-3) / 1e9, 1) for nm in names},
+                # matrix-core utilisation per stage: int8 MFMA operations issued / duration / 5 POP/s dense int8 peak
+                "stage_mfma_frac": {nm: round(mfma_ops[nm] / (stage_ms[nm] * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4)
+                                    for nm in names}}
 
     # ---- correctness of what was timed + CPU baseline (the oracle as it stands) -----------------------------
     torch.cuda.synchronize()
