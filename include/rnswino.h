@@ -84,6 +84,8 @@ enum { RNSWINO_STAGE_U = 0, RNSWINO_STAGE_V = 1, RNSWINO_STAGE_O = 2 };
  * every modulus by exact modular arithmetic; checks (coprimality, invertibility of every point difference,
  * dynamic range); mixed-radix constants; the transform tables the kernels read, uploaded to the current
  * HIP device unless RNSWINO_FLAG_HOST_ONLY.  `desc` is host memory and is copied.  On error *out is NULL.
+ * The plan belongs to that device: rnswino_filter_transform and the rnswino_conv2d calls must be made with the same
+ * device current (RNSWINO_E_INVALID otherwise), on buffers and a stream of that device.
  */
 int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc);
 int rnswino_plan_destroy(rnswino_plan_t *plan);

@@ -84,6 +84,14 @@ inline size_t v_bytes(const Dims &d) { return (size_t)d.n * d.P2 * d.Tp * d.Cp *
 inline size_t o_bytes(const Dims &d) { return (size_t)d.n * d.Q * d.Kp * d.Tp * 4 * elem_bytes(d); }
 inline size_t u_bytes(const Dims &d) { return (size_t)d.n * d.P2 * d.Kp * d.Cp * elem_bytes(d); }
 
+// The plan's tables live on the device that was current when it was made: executing it from another device would hand
+// the kernels pointers of the wrong GPU.
+inline bool on_plan_device(const rnswino_plan_t *plan) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return dev == plan->device;
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? RNSWINO_OK : RNSWINO_E_HIP; }
 
 inline unsigned blocks_for(long long total, int bs) { return (unsigned)((total + bs - 1) / bs); }
@@ -252,6 +260,7 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
   if (!plan || !x_dev || !U_dev || !workspace_dev) return RNSWINO_E_INVALID;
   if (epi == 0 ? !y_dev : !act_dev) return RNSWINO_E_INVALID;
   if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
+  if (!on_plan_device(plan)) return RNSWINO_E_INVALID;
   if (((uintptr_t)U_dev | (uintptr_t)workspace_dev | (uintptr_t)y_dev) & 15) return RNSWINO_E_INVALID;
   if ((uintptr_t)act_dev & 3) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
@@ -353,6 +362,7 @@ size_t rnswino_workspace_bytes(const rnswino_plan_t *plan) {
 int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, void *U_dev, void *stream) {
   if (!plan || !w_dev || !U_dev) return RNSWINO_E_INVALID;
   if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
+  if (!on_plan_device(plan)) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
   const KParams P = make_params(plan);
   const long long total = (long long)d.n * d.Kp * d.Cp;
