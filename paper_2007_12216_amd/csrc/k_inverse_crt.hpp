@@ -107,9 +107,7 @@ __device__ __forceinline__ void crt_convert_fast(const KParams &P, const uint32_
 }
 
 template <int NRES, bool FAST>
-__device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uint32_t (&w)[NRES][4], int rb, int g,
-                                                     const TilePos &tp, int32_t *__restrict__ y) {
-  int val[4];
+__device__ __forceinline__ void k3_convert(const KParams &P, const uint32_t (&w)[NRES][4], int (&val)[4]) {
   if (FAST) {
     crt_convert_fast<NRES>(P, w, val);
   } else if (P.crt24) {               // uniform: one branch per call instead of one per multiply
@@ -118,6 +116,43 @@ __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uin
   } else {
     crt_convert<NRES, false, false>(P, w, val);
   }
+}
+
+// Store of a lane's four outputs for 8 x 8 output tiles (the streaming kernel's unrolled path): the lane's row u
+// and first column v (0 or 4) inside the tile and their offset `off` from the tile's origin in the stored plane do
+// not depend on the unit and are kept in registers by the caller.  Same modes as k3_convert_and_store; the host
+// selects this path for int32 output only when Wo is a multiple of 4.  Must be called by all lanes of a wave.
+__device__ __forceinline__ void k3_store_m8(const KParams &P, const int (&val)[4], int u, int v, uint32_t off,
+                                            const TilePos &tp, int32_t *__restrict__ y) {
+  const bool inside = tp.ok && tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo;
+  if (P.epi == 0) {
+    if (inside) *(v4i *)(y + tp.origin + off) = (v4i){val[0], val[1], val[2], val[3]};
+  } else if (P.epi == 1) {
+    uint32_t packed = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) packed |= ((uint32_t)min(127, max(-128, val[j] >> P.shift)) & 0xFFu) << (8 * j);
+    int8_t *dst = P.act + tp.origin + off;
+    if ((P.Wo & 3) == 0) {
+      if (inside) *(uint32_t *)dst = packed;
+    } else {
+      if (inside) *(uint16_t *)dst = (uint16_t)packed;
+      if (inside && tp.ox0 + v + 2 < P.Wo) *(uint16_t *)(dst + 2) = (uint16_t)(packed >> 16);
+    }
+  } else {
+    // rows u and u + 1 (u even) of the tile sit in lanes l and l ^ 32
+    const int h0 = max(val[0], val[1]), h1 = max(val[2], val[3]);
+    const int o0p = __shfl_xor(h0, 32), o1p = __shfl_xor(h1, 32);
+    const int p0 = min(127, max(-128, max(h0, o0p) >> P.shift)), p1 = min(127, max(-128, max(h1, o1p) >> P.shift));
+    if (inside && (u & 1) == 0)
+      *(uint16_t *)(P.act + tp.origin + off) = (uint16_t)(((uint32_t)p0 & 0xFFu) | (((uint32_t)p1 & 0xFFu) << 8));
+  }
+}
+
+template <int NRES, bool FAST>
+__device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uint32_t (&w)[NRES][4], int rb, int g,
+                                                     const TilePos &tp, int32_t *__restrict__ y) {
+  int val[4];
+  k3_convert<NRES, FAST>(P, w, val);
   const int m = P.m, mm = m * m;
   const float inv_m = 1.0f / (float)m;
   const int o0 = 16 * rb + 4 * g;
@@ -264,7 +299,9 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
 // Grid: min(ceil(units / 4), three blocks per CU) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
 constexpr int K3_STREAM_BLOCKS = 768;   // three resident blocks per CU (register budget) on 256 CUs
 
-template <int NRES, int KS3, bool FAST>
+// M8: 8 x 8 output tiles (four row blocks), the usual case: where a lane's outputs go inside the tile is computed once
+// per kernel instead of once per row block, and the table fragments of a row block sit at immediate LDS offsets.
+template <int NRES, int KS3, bool FAST, bool M8>
 __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const uint32_t *__restrict__ O,
                                                               int32_t *__restrict__ y) {
   extern __shared__ __attribute__((aligned(16))) uint8_t ka_lds[];
@@ -306,11 +343,41 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
   // alternates the two register sets (a copy would wait for every memory operation issued before it).
   const int a0 = FAST ? P.acc0 : 0;                 // 2^22 for the fast conversion
   const v4i acc_start = (v4i){a0, a0, a0, a0};
+  // 8 x 8 tiles: outputs 16 rb + 4 g .. + 3 are row u = 2 rb + (g >> 1), columns v = 4 (g & 1) .. + 3 of the tile; in the
+  // stored plane (pooled: half the rows and columns) row block rb + 1 lies m8_step elements after row block rb
+  const int m8_u0 = g >> 1, m8_v = 4 * (g & 1);
+  const uint32_t m8_step = P.epi == 2 ? (uint32_t)(P.Wo >> 1) : (uint32_t)(2 * P.Wo);
+  const uint32_t m8_off0 = P.epi == 2 ? (uint32_t)(m8_v >> 1) : (uint32_t)(m8_u0 * P.Wo + m8_v);
   auto do_unit = [&](int u, v4i (&o)[NRES][KS3], v4i (&onext)[NRES][KS3]) {
     if (u + nwaves < nunits) load_o(u + nwaves, onext);
     const int kg = u / ntb, taug = (u - kg * ntb) * 16 + (lane & 15);
     const int k = kg / P.TL, tau = taug < P.Tg ? (kg % P.TL) * P.Tg + taug : P.T;   // packed layers: see plan.hpp
     const TilePos tp = tile_position(P, k, tau);
+    if (M8) {
+      // not unrolled: with the four row blocks in one basic block the scheduler requests all their table fragments
+      // at once and the kernel needs twice the registers
+#pragma clang loop unroll(disable)
+      for (int rb = 0; rb < 4; ++rb) {
+        uint32_t w[NRES][4];
+        const uint8_t *ka_rb = ka_lds + lane * 16 + rb * (KS3 * 1024);
+#pragma unroll
+        for (int i = 0; i < NRES; ++i) {
+          v4i acc = acc_start;
+#pragma unroll
+          for (int s = 0; s < KS3; ++s) {
+            const v4i a = *(const v4i *)(ka_rb + (i * 4 * KS3 + s) * 1024);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, o[i][s], acc, 0, 0, 0);
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            w[i][j] = FAST ? (uint32_t)acc[j] : mod_near_plus_p(acc[j], P.inv_p[i], -P.p[i], P.bias_p[i]);
+        }
+        int val[4];
+        k3_convert<NRES, FAST>(P, w, val);
+        k3_store_m8(P, val, 2 * rb + m8_u0, m8_v, m8_off0 + rb * m8_step, tp, y);
+      }
+      return;
+    }
     for (int rb = 0; rb < P.RB3; ++rb) {
       uint32_t w[NRES][4];
 #pragma unroll

@@ -209,7 +209,10 @@ void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, in
   const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
   const dim3 grid((unsigned)(blocks < max_blocks ? blocks : max_blocks));
   const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
-  auto kern = P.fastcrt ? k3_inverse_crt_stream<NRES, KS3, true> : k3_inverse_crt_stream<NRES, KS3, false>;
+  // 8 x 8 tiles take the unrolled path (int32 output: only with rows that keep four outputs 16-byte aligned)
+  const bool m8 = d.m == 8 && (P.epi != 0 || (d.Wo & 3) == 0);
+  auto kern = P.fastcrt ? (m8 ? k3_inverse_crt_stream<NRES, KS3, true, true> : k3_inverse_crt_stream<NRES, KS3, true, false>)
+                        : (m8 ? k3_inverse_crt_stream<NRES, KS3, false, true> : k3_inverse_crt_stream<NRES, KS3, false, false>);
   if (tm.start || tm.stop)
     hipExtLaunchKernelGGL(kern, grid, dim3(256), lds, st, tm.start, tm.stop, 0, P, O, y);
   else
