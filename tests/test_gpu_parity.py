@@ -343,3 +343,61 @@ def test_random_shapes_are_bit_exact(case):
     w = si.int8_tensor(502, (K, C, r, r))
     _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
     assert np.array_equal(y, direct_conv2d(x, w, pad))
+
+
+def test_two_streams_with_their_own_workspaces():
+    """One plan and one transformed filter, two calls in flight on two streams, each with its own workspace and output:
+    the entry point keeps no state between calls, so both results are the oracle's."""
+    print("two streams", flush=True)
+    from paper_2007_12216_amd.layer import ConvLayer
+    N, C, K, H, W, r, m, pad, moduli = 2, 70, 40, 28, 28, 3, 8, 1, (251, 241, 239, 233)
+    w = si.int8_tensor(77, (K, C, r, r))
+    xs = [si.int8_tensor(78 + j, (N, C, H, W)) for j in range(2)]
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli)
+    layer.set_weights(w)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]          # default priority
+    xd = [torch.from_numpy(x).to("cuda:0") for x in xs]
+    ws = [torch.empty_like(layer.workspace) for _ in range(2)]
+    ys = [torch.empty_like(layer.y) for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for j in range(2):
+            rn.rnswino_conv2d(layer.plan, xd[j], layer.U, ys[j], ws[j], streams[j].cuda_stream)
+    torch.cuda.synchronize()
+    for j in range(2):
+        assert np.array_equal(ys[j].cpu().numpy(), direct_conv2d(xs[j], w, pad))
+
+
+def test_captured_graph_replays_match_the_eager_result():
+    """rnswino_conv2d neither allocates nor synchronises, so its three launches can be captured into a HIP graph; every
+    replay (with eager work and synchronisations of the program's own in between) must give the eager result."""
+    print("graph capture", flush=True)
+    from paper_2007_12216_amd.layer import ConvLayer
+    N, C, K, H, W, r, m, pad, moduli = 1, 64, 32, 24, 24, 3, 8, 1, (251, 241, 239, 233)
+    w = si.int8_tensor(91, (K, C, r, r))
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli)
+    layer.set_weights(w)
+    x_static = torch.zeros((N, C, H, W), dtype=torch.int8, device="cuda:0")
+    y_static = torch.empty_like(layer.y)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                  # warm-up on the capture stream, as graph capture asks
+        rn.rnswino_conv2d(layer.plan, x_static, layer.U, y_static, layer.workspace, side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rn.rnswino_conv2d(layer.plan, x_static, layer.U, y_static, layer.workspace,
+                          torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        x = si.int8_tensor(100 + rep, (N, C, H, W))
+        x_static.copy_(torch.from_numpy(x).to("cuda:0"))
+        eager = layer.forward(x_static).clone()                    # eager call between the replays (shares the workspace: ordered by the stream)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = direct_conv2d(x, w, pad)
+        assert np.array_equal(eager.cpu().numpy(), ref)
+        assert np.array_equal(y_static.cpu().numpy(), ref), f"replay {rep}"
