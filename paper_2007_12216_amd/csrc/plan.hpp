@@ -67,4 +67,5 @@ struct rnswino_plan_s {
   // offsets (bytes) into d_tables
   size_t off_G;                             // int32 G matrices [n][t*r] (filter transform)
   size_t off_KB, off_KA;                    // int8 Kronecker tables of the input / inverse transform
+  void *kparams;                            // the kernels' parameter block (rnswino::KParams), built once with the plan
 };

@@ -71,10 +71,12 @@ KParams make_params(const rnswino_plan_t *pl) {
     }
   }
   P.prod_mod32 = pl->prod_mod32;
-  const char *base = (const char *)pl->d_tables;
-  P.G = (const int32_t *)(base + pl->off_G);
-  P.KB = (const int8_t *)(base + pl->off_KB);
-  P.KA = (const int8_t *)(base + pl->off_KA);
+  if (pl->d_tables) {                   // host-only plans are never executed: their table pointers stay null
+    const char *base = (const char *)pl->d_tables;
+    P.G = (const int32_t *)(base + pl->off_G);
+    P.KB = (const int8_t *)(base + pl->off_KB);
+    P.KA = (const int8_t *)(base + pl->off_KA);
+  }
   return P;
 }
 
@@ -267,7 +269,7 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
   if (((uintptr_t)U_dev | (uintptr_t)workspace_dev | (uintptr_t)y_dev) & 15) return RNSWINO_E_INVALID;
   if ((uintptr_t)act_dev & 3) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
-  KParams P = make_params(plan);
+  KParams P = *(const KParams *)plan->kparams;    // per call only the output mode differs
   P.epi = epi; P.shift = shift; P.act = act_dev;
   hipStream_t st = (hipStream_t)stream;
   int8_t *Vp = (int8_t *)workspace_dev;
@@ -302,6 +304,7 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   pl->n_cus = 0;
   pl->d_tables = nullptr;
   pl->d_tables_bytes = 0;
+  pl->kparams = nullptr;
   int rc = validate_desc(*desc, pl->dims);
   if (rc != RNSWINO_OK) { delete pl; return rc; }
   const Dims &d = pl->dims;
@@ -338,6 +341,8 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
       else (void)hipGetLastError();
     }
   }
+  pl->kparams = new (std::nothrow) KParams(make_params(pl));
+  if (!pl->kparams) { (void)rnswino_plan_destroy(pl); return RNSWINO_E_INVALID; }
   *out = pl;
   return RNSWINO_OK;
 }
@@ -346,6 +351,7 @@ int rnswino_plan_destroy(rnswino_plan_t *plan) {
   if (!plan) return RNSWINO_E_INVALID;
   int rc = RNSWINO_OK;
   if (plan->d_tables && hipFree(plan->d_tables) != hipSuccess) { (void)hipGetLastError(); rc = RNSWINO_E_HIP; }
+  delete (KParams *)plan->kparams;
   delete plan;
   return rc;
 }
@@ -367,7 +373,7 @@ int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, vo
   if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
   if (!on_plan_device(plan)) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
-  const KParams P = make_params(plan);
+  const KParams P = *(const KParams *)plan->kparams;
   const long long total = (long long)d.n * d.Kp * d.Cp;
   hipStream_t st = (hipStream_t)stream;
   if (d.wide)
