@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size
 # (profiles/conv2d_config2_hbm_traffic.md).  Counters cannot be read from inside this script, so the figures are
 # recorded here for the workload they were taken on; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {2: {"input_transform": 7.58e6, "residue_gemm": 39.37e6, "inverse_transform_mrc": 10.11e6}}
+MEASURED_TRAFFIC_BYTES = {2: {"input_transform": 7.56e6, "residue_gemm": 39.37e6, "inverse_transform_mrc": 10.11e6}}
 ROTATION_BYTES = 640 << 20      # operands cycled through in the cold loop (> 256 MB Infinity Cache + 32 MB L2)
 
 
