@@ -148,7 +148,9 @@ void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_
   const long long pl = WIDE ? 2 : 1;
   const long long nxh = (d.n * d.Q + 7) / 8, gy = (d.Kp + 16 * RM - 1) / (16 * RM), gz = (d.Tp / 16 + NTB - 1) / NTB;
   const long long u_x = 4LL * d.Kp * d.Cp * pl, v_slice = 4LL * 16 * NTB * d.Cp * pl;
-  long long xgroup = gz == 1 ? nxh : (3LL << 20) / (u_x + 2 * v_slice);
+  // With a single tile block nothing of U is used twice: one x at a time, so that the workgroups in flight on an XCD
+  // read neighbouring row blocks of one U slab (measured: 3-7 % faster than walking over all x at once).
+  long long xgroup = gz == 1 ? 1 : (3LL << 20) / (u_x + 2 * v_slice);
   xgroup = xgroup < 1 ? 1 : (xgroup > nxh ? nxh : xgroup);
   if (xgroup > 1 && xgroup < nxh && (xgroup & 1) == 0) --xgroup;   // measured: even group sizes run into each other in the L2 channels
   const long long blocks = 8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz;
