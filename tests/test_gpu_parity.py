@@ -401,3 +401,20 @@ def test_captured_graph_replays_match_the_eager_result():
         ref = direct_conv2d(x, w, pad)
         assert np.array_equal(eager.cpu().numpy(), ref)
         assert np.array_equal(y_static.cpu().numpy(), ref), f"replay {rep}"
+
+
+def test_the_papers_vgg16_setting_with_a_trusted_range():
+    """Section 8 runs VGG16 with F(14x14,3x3) over RNS(251,241,239) on layers of up to 512 channels, trusting a measured
+    output range instead of the worst case (which three 8-bit moduli cover only up to 49 channels).  Same setting here
+    on a 256-channel 28x28 layer: the plan needs the unchecked-range flag, the outputs of the seeded data stay inside
+    the dynamic range, and the result is the exact convolution."""
+    print("paper setting", flush=True)
+    N, C, K, H, W, r, m, pad, moduli = 1, 256, 64, 28, 28, 3, 14, 1, (251, 241, 239)
+    with pytest.raises(rn.RnsWinoError):
+        rn.rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags=rn.FLAG_HOST_ONLY)
+    x = si.int8_tensor(8801, (N, C, H, W))
+    w = si.int8_tensor(8802, (K, C, r, r))
+    ref = direct_conv2d(x, w, pad)
+    assert np.abs(ref.astype(np.int64)).max() <= (251 * 241 * 239 - 1) // 2
+    _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w, flags=rn.FLAG_ALLOW_UNCHECKED_RANGE)
+    assert np.array_equal(y, ref)
