@@ -130,6 +130,15 @@ def bench_stack(args, dev):
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / K_steps
     ops = stack.direct_ops()
+    # algorithmic HBM bytes of one pass: per layer x + 2 V + U + 2 O + the int8 activations it stores (after pooling)
+    pass_bytes = 0
+    for l, p, a in zip(layers, stack.plans, stack.act):
+        n, t2 = len(l["moduli"]), p.t * p.t
+        pass_bytes += (l["N"] * l["C"] * l["H"] * l["W"] + 2 * n * t2 * p.T * l["C"] + n * t2 * l["K"] * l["C"]
+                       + 2 * n * t2 * l["K"] * p.T + a.numel())
+    roofline = {"bound": "hbm", "kernel": "whole pass (13 layers x 3 launches)", "achieved": round(pass_bytes / sec / 1e9, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pass_bytes / sec / 1e9 / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes": pass_bytes}
     cpu, bit_exact = None, None
     if not args.no_cpu_baseline:
         from oracle import direct_conv2d, requant_shift_clamp, maxpool2x2, num_threads
@@ -150,7 +159,7 @@ def bench_stack(args, dev):
         "config": {"workload": "config5: VGG16 conv stack, N=8, 224x224, 13 layers, F(8x8,3x3), shift/clamp + 2x2 max-pool "
                                "fused into the inverse transform", "direct_conv_GOP": round(ops / 1e9, 2),
                    "bit_exact_vs_oracle": bit_exact},
-        "roofline": None, "cpu_baseline": cpu}))
+        "roofline": roofline, "cpu_baseline": cpu}))
 
 
 def main():
