@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
 #pragma unroll
           for (int tb = 0; tb < NTB; ++tb) {
             const bool start = FIRST && s == 0;
-            if (WIDE) {
+            if constexpr (WIDE) {
               acc[0][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][0], b[s][tb][0], start ? zero : acc[0][rm][tb], 0, 0, 0);
               acc[1][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][0], b[s][tb][PL - 1], start ? zero : acc[1][rm][tb], 0, 0, 0);
               acc[1][rm][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s][rm][PL - 1], b[s][tb][0], acc[1][rm][tb], 0, 0, 0);
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int at = ((rm * 16 + j) * PITCH + tb * 16 * PL) * 4;   // row rm*16 + 4*(lane>>4) + j, column tb*16 + lane%16
-        if (WIDE) {
+        if constexpr (WIDE) {
           const long long tot = (long long)acc[0][rm][tb][j] * 65536 + (long long)acc[1][rm][tb][j] * 256 +
                                 (long long)acc[NACC - 1][rm][tb][j];
           const int v = storable16(mod_near64(tot, P.inv_pd[i], p), p);
