@@ -123,8 +123,9 @@ int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *
 /*
  * rnswino_conv2d fused with the layer glue of rnswino_requant_pool: the inverse-transform kernel writes
  *   a = clamp(floor(y / 2^shift), -128, 127)   (int8 [N][K][Ho][Wo]), after a 2x2 stride-2 max-pool when pool != 0
- * (int8 [N][K][Ho/2][Wo/2]), and the int32 y is never stored.  Supported when m is 4 or 8, Wo is even, and,
- * for pooling, Wo is a multiple of 4 and Ho is even; otherwise RNSWINO_E_UNSUPPORTED (use rnswino_conv2d + rnswino_requant_pool).
+ * (int8 [N][K][Ho/2][Wo/2]), and the int32 y is never stored.  Without pooling every tile size is supported (m of 4 or 8
+ * with an even Wo stores two or four bytes at a time, anything else single bytes); pooling needs m of 4 or 8, Wo a multiple
+ * of 4 and an even Ho, otherwise RNSWINO_E_UNSUPPORTED (use rnswino_conv2d + rnswino_requant_pool).
  * a_dev must be 4-byte aligned.  Not part of the paper's method (the 13-layer stack workload needs it).
  */
 int rnswino_conv2d_requant(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int8_t *a_dev,

@@ -156,8 +156,22 @@ __device__ __forceinline__ void k3_convert_and_store(const KParams &P, const uin
   const int m = P.m, mm = m * m;
   const float inv_m = 1.0f / (float)m;
   const int o0 = 16 * rb + 4 * g;
+  if (P.epi == 1 && (((m & 3) != 0) || (P.Wo & 1))) {
+    // any other tile size or an odd row length: the four outputs may sit in two rows of the tile and at any byte
+    // alignment, so each is stored as a byte of its own
+    if (!tp.ok) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int o = o0 + j;
+      const int u = (int)(((float)o + 0.5f) * inv_m);
+      const int v = o - u * m;
+      if (o < mm && tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo)
+        P.act[tp.origin + (uint32_t)(u * P.Wo + v)] = (int8_t)min(127, max(-128, val[j] >> P.shift));
+    }
+    return;
+  }
   if (P.epi != 0) {
-    // host guarantees m in {4, 8}, even Wo; when pooling Wo % 4 == 0 and even Ho
+    // here m is 4 or 8 and Wo even (pooling: the host also guarantees Wo % 4 == 0 and an even Ho)
     const int u = (int)(((float)o0 + 0.5f) * inv_m);
     const int v = o0 - u * m;
     const bool inside = tp.ok && o0 < mm && tp.oy0 + u < P.Ho && tp.ox0 + v < P.Wo;

@@ -213,8 +213,9 @@ void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, in
   const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
   const dim3 grid((unsigned)(blocks < max_blocks ? blocks : max_blocks));
   const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
-  // 8 x 8 tiles take the unrolled path (int32 output: only with rows that keep four outputs 16-byte aligned)
-  const bool m8 = d.m == 8 && (P.epi != 0 || (d.Wo & 3) == 0);
+  // 8 x 8 tiles take their own path (int32 output: only with rows that keep four outputs 16-byte aligned; int8 output:
+  // only with an even row length)
+  const bool m8 = d.m == 8 && (P.epi == 0 ? (d.Wo & 3) == 0 : (d.Wo & 1) == 0);
   auto kern = P.fastcrt ? (m8 ? k3_inverse_crt_stream<NRES, KS3, true, true> : k3_inverse_crt_stream<NRES, KS3, true, false>)
                         : (m8 ? k3_inverse_crt_stream<NRES, KS3, false, true> : k3_inverse_crt_stream<NRES, KS3, false, false>);
   if (tm.start || tm.stop)
@@ -394,7 +395,8 @@ int rnswino_conv2d_requant(const rnswino_plan_t *plan, const int8_t *x_dev, cons
                            int32_t shift, int32_t pool, void *workspace_dev, void *stream) {
   if (!plan || shift < 0 || shift > 31) return RNSWINO_E_INVALID;
   const Dims &d = plan->dims;
-  if ((d.m != 4 && d.m != 8) || (d.Wo & 1) || (pool && ((d.Wo & 3) || (d.Ho & 1)))) return RNSWINO_E_UNSUPPORTED;
+  // pooling inside the kernel pairs rows and columns of one output tile: tiles of 4 or 8, whole pooling windows per row
+  if (pool && ((d.m != 4 && d.m != 8) || (d.Wo & 3) || (d.Ho & 1))) return RNSWINO_E_UNSUPPORTED;
   return conv2d_impl(plan, x_dev, U_dev, nullptr, workspace_dev, stream, nullptr, pool ? 2 : 1, shift, a_dev);
 }
 

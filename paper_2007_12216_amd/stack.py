@@ -48,7 +48,7 @@ class ConvStack:
         a = x
         last = len(self.cfg) - 1
         for li, (l, p, U, out) in enumerate(zip(self.cfg, self.plans, self.U, self.act)):
-            fusable = p.m in (4, 8) and p.Wo % 2 == 0 and (not l["pool"] or (p.Ho % 2 == 0 and p.Wo % 4 == 0))
+            fusable = not l["pool"] or (p.m in (4, 8) and p.Ho % 2 == 0 and p.Wo % 4 == 0)
             if fuse and fusable and not (keep_last_y and li == last):
                 B.rnswino_conv2d_requant(p, a, U, out, l["shift"], l["pool"], self.workspace, st)
             else:

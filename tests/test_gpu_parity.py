@@ -233,7 +233,9 @@ def test_vgg16_stack_full_size():
 
 
 @pytest.mark.parametrize("m,pool,W", [(8, False, 28), (8, True, 28), (4, False, 28), (4, True, 28),
-                                      (8, False, 14), (4, False, 30), (8, False, 22)])   # rows not a multiple of 4 bytes
+                                      (8, False, 14), (4, False, 30), (8, False, 22),    # rows not a multiple of 4 bytes
+                                      (7, False, 28), (6, False, 27), (10, False, 21), (8, False, 21), (14, False, 28),
+                                      (2, False, 9)])                                    # byte stores: any tile, odd rows
 def test_fused_requant_matches_the_oracle_glue(m, pool, W):
     from oracle import requant_shift_clamp, maxpool2x2
     print("fused requant", m, pool, W, flush=True)
@@ -254,12 +256,14 @@ def test_fused_requant_matches_the_oracle_glue(m, pool, W):
     assert np.array_equal(a.cpu().numpy(), ref)
 
 
-def test_fused_requant_refuses_unsupported_tiles():
+def test_fused_pooling_refuses_unsupported_tiles():
+    """Pooling inside the kernel needs output tiles of 4 or 8; without pooling every tile size is taken."""
     from paper_2007_12216_amd.layer import ConvLayer
     layer = ConvLayer(1, 4, 4, 12, 12, 3, 10, 1, (253, 251, 247))
-    a = torch.empty((1, 4, 12, 12), dtype=torch.int8, device="cuda:0")
+    x = torch.zeros((1, 4, 12, 12), dtype=torch.int8, device="cuda:0")
+    a = torch.empty((1, 4, 6, 6), dtype=torch.int8, device="cuda:0")
     with pytest.raises(rn.RnsWinoError) as e:
-        rn.rnswino_conv2d_requant(layer.plan, a, layer.U, a, 9, False, layer.workspace, 0)
+        rn.rnswino_conv2d_requant(layer.plan, x, layer.U, a, 9, True, layer.workspace, 0)
     assert e.value.code == -2
 
 
