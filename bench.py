@@ -118,7 +118,7 @@ def bench_stack(args, dev):
     layers = si.vgg16_stack(batch=8, hw=224)
     weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
     x_np = si.int8_tensor(si.VGG16_SEED_X, (8, 3, 224, 224))
-    stack = ConvStack(layers)
+    stack = ConvStack(layers, measured_tiles=args.measured_tiles)
     stack.set_weights(weights)
     x = torch.from_numpy(x_np).to(dev)
     for _ in range(W_steps):
@@ -156,8 +156,10 @@ def bench_stack(args, dev):
         "metric": "effective INT8 TOPS per conv layer (direct-conv ops/s)", "value": round(ops / sec / 1e12, 3),
         "unit": "TOPS", "n_gpus": 1, "steps": K_steps, "warmup": W_steps, "ms_per_step": round(sec * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "config5: VGG16 conv stack, N=8, 224x224, 13 layers, F(8x8,3x3), shift/clamp + 2x2 max-pool "
-                               "fused into the inverse transform", "direct_conv_GOP": round(ops / 1e9, 2),
+        "config": {"workload": "config5: VGG16 conv stack, N=8, 224x224, 13 layers, " +
+                               ("output tile measured per layer" if args.measured_tiles else "F(8x8,3x3)") +
+                               ", shift/clamp + 2x2 max-pool fused into the inverse transform",
+                   "output_tiles": [l["m"] for l in stack.cfg], "direct_conv_GOP": round(ops / 1e9, 2),
                    "bit_exact_vs_oracle": bit_exact},
         "roofline": roofline, "cpu_baseline": cpu}))
 
@@ -171,6 +173,8 @@ def main():
                     help="single-layer workload 1-4 (default 2, the one the metric is quoted on), or 5: the 13-layer stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="also time the loop on one operand set (cache-warm)")
+    ap.add_argument("--measured-tiles", action="store_true",
+                    help="workload 5 only: pick every layer's output tile by timing the candidates (default: F(8x8,3x3) as specified)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)

@@ -34,10 +34,18 @@ def candidate_tiles(r: int, moduli) -> list[int]:
     return out
 
 
-def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: int = 20, warmup: int = 3,
-                       device="cuda:0"):
-    """Times rnswino_conv2d for every candidate m on synthetic int8 data of the layer's shape.
+def fused_glue_supported(m: int, Ho: int, Wo: int, pool: bool) -> bool:
+    """Whether rnswino_conv2d_requant takes this layer (pooling inside the kernel needs tiles of 4 or 8, Wo % 4 == 0 and
+    an even Ho; without pooling every tile does)."""
+    return (not pool) or (m in (4, 8) and Ho % 2 == 0 and Wo % 4 == 0)
 
+
+def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: int = 20, warmup: int = 3,
+                       device="cuda:0", glue=None):
+    """Times the layer for every candidate m on synthetic int8 data of the layer's shape.
+
+    Without `glue` a timed step is one rnswino_conv2d call (int32 output).  With glue = (shift, pool) it is the layer as
+    a chain runs it: rnswino_conv2d_requant where the library supports it, else rnswino_conv2d + rnswino_requant_pool.
     Returns (best_m, {m: microseconds per call}).  Candidates the plan refuses (range, size limits) are left out.
     """
     if not torch.cuda.is_available():
@@ -55,13 +63,25 @@ def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: in
         except B.RnsWinoError:
             continue
         layer.set_weights(w)
+        step = lambda: layer.forward(x)
+        if glue is not None:
+            shift, pool = glue
+            p = layer.plan
+            act = torch.empty((N, K, p.Ho // 2, p.Wo // 2) if pool else (N, K, p.Ho, p.Wo), dtype=torch.int8, device=dev)
+            st = torch.cuda.current_stream(dev).cuda_stream
+            if fused_glue_supported(m, p.Ho, p.Wo, bool(pool)):
+                step = lambda: B.rnswino_conv2d_requant(p, x, layer.U, act, shift, pool, layer.workspace, st)
+            else:
+                def step():
+                    B.rnswino_conv2d(p, x, layer.U, layer.y, layer.workspace, st)
+                    B.rnswino_requant_pool(layer.y, act, N * K, p.Ho, p.Wo, shift, pool, st)
         for _ in range(warmup):
-            layer.forward(x)
+            step()
         start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize(dev)
         start.record()
         for _ in range(iters):
-            layer.forward(x)
+            step()
         stop.record()
         torch.cuda.synchronize(dev)
         times[m] = start.elapsed_time(stop) * 1e3 / iters

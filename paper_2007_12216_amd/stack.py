@@ -6,15 +6,29 @@ import numpy as np
 import torch
 
 from . import binding as B
+from .select import fused_glue_supported
 
 
 class ConvStack:
-    def __init__(self, layers, device="cuda:0"):
-        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool (see synth_inputs.vgg16_stack)."""
+    def __init__(self, layers, device="cuda:0", measured_tiles: bool = False):
+        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool (see synth_inputs.vgg16_stack).
+
+        measured_tiles: replace every layer's output tile m by the fastest one for its shape, timed on the device with the
+        layer's own glue (the paper picks the tile per layer from operation counts and measured GEMM throughput, its
+        section 6; here the whole layer is timed).  The result does not depend on m: it is the exact convolution."""
         if not torch.cuda.is_available():
             raise RuntimeError("rnswino needs a GPU: there is no CPU execution path")
         self.device = torch.device(device)
         self.cfg = [dict(l) for l in layers]
+        if measured_tiles:
+            from .select import select_output_tile
+            chosen = {}
+            for l in self.cfg:
+                key = (l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["pad"], tuple(l["moduli"]), l["shift"], bool(l["pool"]))
+                if key not in chosen:
+                    chosen[key], _ = select_output_tile(l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["pad"], l["moduli"],
+                                                        iters=10, device=self.device, glue=(l["shift"], l["pool"]))
+                l["m"] = chosen[key]
         self.plans, self.U, self.act = [], [], []
         ws_bytes, y_elems = 0, 0
         with torch.cuda.device(self.device):
@@ -48,7 +62,7 @@ class ConvStack:
         a = x
         last = len(self.cfg) - 1
         for li, (l, p, U, out) in enumerate(zip(self.cfg, self.plans, self.U, self.act)):
-            fusable = not l["pool"] or (p.m in (4, 8) and p.Ho % 2 == 0 and p.Wo % 4 == 0)
+            fusable = fused_glue_supported(p.m, p.Ho, p.Wo, bool(l["pool"]))
             if fuse and fusable and not (keep_last_y and li == last):
                 B.rnswino_conv2d_requant(p, a, U, out, l["shift"], l["pool"], self.workspace, st)
             else:

@@ -214,6 +214,26 @@ def test_vgg16_stack_reduced_plane(batch, hw, fuse):
     assert (last != 0).mean() > 0.5 and (np.abs(last) >= 127).mean() < 0.5
 
 
+def test_vgg16_stack_with_measured_tiles():
+    """Every layer's output tile picked by timing the candidates on the device: whatever tiles win, every layer's
+    activations are those of the CPU chain (the result does not depend on the tile)."""
+    from paper_2007_12216_amd.stack import ConvStack
+    print("stack measured tiles", flush=True)
+    batch, hw = 2, 64
+    layers = si.vgg16_stack(batch=batch, hw=hw)
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
+    stack = ConvStack(layers, measured_tiles=True)
+    print("tiles", [l["m"] for l in stack.cfg], flush=True)
+    assert all(2 <= l["m"] <= 14 for l in stack.cfg)
+    stack.set_weights(weights)
+    stack.forward(torch.from_numpy(x).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref_acts, _ = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+
+
 def test_vgg16_stack_full_size():
     """Workload 5: batch 8, 224x224, all 13 layers; every layer's activations bit-exact against the CPU chain."""
     from paper_2007_12216_amd.stack import ConvStack
