@@ -41,7 +41,7 @@ def fused_glue_supported(m: int, Ho: int, Wo: int, pool: bool) -> bool:
 
 
 def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: int = 20, warmup: int = 3,
-                       device="cuda:0", glue=None):
+                       device="cuda:0", glue=None, flags: int = 0):
     """Times the layer for every candidate m on synthetic int8 data of the layer's shape.
 
     Without `glue` a timed step is one rnswino_conv2d call (int32 output).  With glue = (shift, pool) it is the layer as
@@ -52,14 +52,14 @@ def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: in
         raise RuntimeError("rnswino needs a GPU: there is no CPU execution path")
     dev = torch.device(device)
     if candidates is None:
-        candidates = candidate_tiles(r, moduli)
+        candidates = candidate_tiles(r, moduli)   # (the range is checked again, with the layer's C, by the plan below)
     gen = torch.Generator(device="cpu").manual_seed(12216)
     x = torch.randint(-128, 128, (N, C, H, W), dtype=torch.int8, generator=gen).to(dev)
     w = torch.randint(-128, 128, (K, C, r, r), dtype=torch.int8, generator=gen)
     times = {}
     for m in candidates:
         try:
-            layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, device=dev)
+            layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, flags, device=dev)
         except B.RnsWinoError:
             continue
         layer.set_weights(w)

@@ -11,7 +11,8 @@ from .select import fused_glue_supported
 
 class ConvStack:
     def __init__(self, layers, device="cuda:0", measured_tiles: bool = False):
-        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool (see synth_inputs.vgg16_stack).
+        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool and optionally flags (plan flags)
+        (see synth_inputs.vgg16_stack).
 
         measured_tiles: replace every layer's output tile m by the fastest one for its shape, timed on the device with the
         layer's own glue (the paper picks the tile per layer from operation counts and measured GEMM throughput, its
@@ -27,13 +28,15 @@ class ConvStack:
                 key = (l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["pad"], tuple(l["moduli"]), l["shift"], bool(l["pool"]))
                 if key not in chosen:
                     chosen[key], _ = select_output_tile(l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["pad"], l["moduli"],
-                                                        iters=10, device=self.device, glue=(l["shift"], l["pool"]))
+                                                        iters=10, device=self.device, glue=(l["shift"], l["pool"]),
+                                                        flags=l.get("flags", 0))
                 l["m"] = chosen[key]
         self.plans, self.U, self.act = [], [], []
         ws_bytes, y_elems = 0, 0
         with torch.cuda.device(self.device):
             for l in self.cfg:
-                p = B.rnswino_plan(l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["m"], l["pad"], l["moduli"])
+                p = B.rnswino_plan(l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["m"], l["pad"], l["moduli"],
+                                   l.get("flags", 0))
                 self.plans.append(p)
                 self.U.append(torch.empty(B.rnswino_filter_bytes(p), dtype=torch.uint8, device=self.device))
                 ws_bytes = max(ws_bytes, B.rnswino_workspace_bytes(p))

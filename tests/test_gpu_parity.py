@@ -234,6 +234,26 @@ def test_vgg16_stack_with_measured_tiles():
         assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
 
 
+def test_vgg16_stack_in_the_papers_setting():
+    """Three 8-bit moduli on every layer with the range trusted (section 8 of the paper) instead of four from the worst-case
+    bound: the outputs of the seeded data stay inside the dynamic range, so the chain is still the oracle's."""
+    from paper_2007_12216_amd.stack import ConvStack
+    print("stack trusted range", flush=True)
+    batch, hw = 2, 32
+    layers = si.vgg16_stack(batch=batch, hw=hw)
+    for l in layers:
+        l["moduli"], l["flags"] = (251, 241, 239), rn.FLAG_ALLOW_UNCHECKED_RANGE
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
+    stack = ConvStack(layers)
+    stack.set_weights(weights)
+    stack.forward(torch.from_numpy(x).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref_acts, _ = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+
+
 def test_vgg16_stack_full_size():
     """Workload 5: batch 8, 224x224, all 13 layers; every layer's activations bit-exact against the CPU chain."""
     from paper_2007_12216_amd.stack import ConvStack
