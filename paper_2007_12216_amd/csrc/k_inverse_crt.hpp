@@ -22,7 +22,8 @@
 // output; the constants that undo the offset sit in KParams (crt_sum0, crt_fs0).  The binary32 sum carries an
 // error of a few hundredths (bounded on the host from the moduli), so the host enables this path only when the
 // layer's worst case keeps |y/P| that far below 1/2 -- true for every layer whose moduli were chosen by the
-// range bound with a little room, e.g. all five benchmark workloads.
+// range bound with a little room, e.g. all five benchmark workloads.  Otherwise (KParams::fastcrt == 2) the same sum
+// is taken in binary64, which is exact enough for every result the moduli can represent.
 //
 // Block = one unit of 16 consecutive (k, tile) pairs and four 16-output row blocks rb = 4*blockIdx.y + wave; every
 // wave loads the O operand itself (the copies hit in L1): a wave-uniform row of O plus a 32-bit lane offset per
@@ -106,10 +107,30 @@ __device__ __forceinline__ void crt_convert_fast(const KParams &P, const uint32_
   }
 }
 
+// The same with the quotient in binary64: the sum then carries an error below 1e-10 and finds the quotient for every
+// result in [-(P-1)/2, (P-1)/2] (the host checks its bound against 1/(2P)), so layers at the edge of the dynamic
+// range and plans with an unchecked range take this form.
+template <int NRES>
+__device__ __forceinline__ void crt_convert_fast64(const KParams &P, const uint32_t (&w)[NRES][4], int (&val)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t sum = P.crt_sum0;
+    double fs = P.crt_fs0d;
+#pragma unroll
+    for (int i = 0; i < NRES; ++i) {
+      sum += __umul24(P.crt_c[i], w[i][j]);
+      fs = __builtin_fma((double)w[i][j], P.inv_pd[i], fs);
+    }
+    const int kk = __double2int_rn(fs);
+    val[j] = (int)(sum - P.prod_mod32 * (uint32_t)kk);
+  }
+}
+
 template <int NRES, bool FAST>
 __device__ __forceinline__ void k3_convert(const KParams &P, const uint32_t (&w)[NRES][4], int (&val)[4]) {
   if (FAST) {
-    crt_convert_fast<NRES>(P, w, val);
+    if (P.fastcrt == 2) crt_convert_fast64<NRES>(P, w, val);   // uniform
+    else crt_convert_fast<NRES>(P, w, val);
   } else if (P.crt24) {               // uniform: one branch per call instead of one per multiply
     if (P.quot32) crt_convert<NRES, true, true>(P, w, val);
     else crt_convert<NRES, true, false>(P, w, val);

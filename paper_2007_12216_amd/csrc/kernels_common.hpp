@@ -30,9 +30,10 @@ struct KParams {
   int quot32;                 // the layer's worst-case |y| is at most 0.45 prod p_i: binary32 finds the CRT quotient
   int bias_p[8];              // p_i * 2^22 + p_i (8-bit moduli), see mod_near_plus_p()
   // fast conversion out of the RNS (k_inverse_crt.hpp): unreduced accumulators that start at acc0 = 2^22
-  int fastcrt, acc0;
+  int fastcrt, acc0;          // fastcrt: 0 = off, 1 = binary32 quotient, 2 = binary64 quotient
   uint32_t crt_sum0;          // -acc0 * sum_i prod_{l != i} p_l mod 2^32
   float crt_fs0;              // -acc0 * sum_i 1/p_i
+  double crt_fs0d;            // the same in binary64
   // fused re-quantisation in the inverse-transform kernel (chained layers): 0 = store int32 y,
   // 1 = store int8 clamp(y >> shift), 2 = the same after a 2x2 stride-2 max-pool
   int epi, shift;

@@ -55,18 +55,26 @@ KParams make_params(const rnswino_plan_t *pl) {
     // takes n + 1 roundings of at most half an ulp of 2B each, and the rounded 1/p_i add at most 2B 2^-23 in all.
     // Enabled when the layer's worst case leaves twice that error below 0.49 - |y|/P.
     if (!d.wide && P.crt24 && prod < cap) {
-      double B = 0.0;
+      long double Bl = 0.0L;             // extended precision: the one rounding to binary64 is counted below
       uint32_t c32 = 0;
-      for (int i = 0; i < d.n; ++i) { B += 4194304.0 / (double)pl->desc.moduli[i]; c32 += pl->crt_c[i]; }
+      for (int i = 0; i < d.n; ++i) { Bl += 4194304.0L / (long double)pl->desc.moduli[i]; c32 += pl->crt_c[i]; }
+      const double B = (double)Bl;
       int e = 0;
       std::frexp(2.0 * B, &e);                                   // 2B = f * 2^e, f in [0.5, 1)
       const double half_ulp = std::ldexp(1.0, e - 24 - 1);      // binary32: ulp = 2^(e - 24)
       const double err = (d.n + 1) * half_ulp + 2.0 * B * std::ldexp(1.0, -23);
-      if ((double)worst / (double)prod + 2.0 * err <= 0.49) {
-        P.fastcrt = 1;
+      // The same sum in binary64 (ulp = 2^(e64 - 53)) must find the quotient for every |y| <= (P - 1)/2, i.e. stay
+      // within 1/(2P) of the true value: twice its error bound has to fit.
+      int e64 = 0;
+      std::frexp(B, &e64);                                       // every partial sum lies in [-B, B], B < 2^e64
+      const double err64 = (d.n + 1) * std::ldexp(1.0, e64 - 53 - 1) + 2.0 * B * std::ldexp(1.0, -52);
+      if ((double)worst / (double)prod + 2.0 * err <= 0.49) P.fastcrt = 1;
+      else if (2.0 * err64 <= 0.5 / (double)prod) P.fastcrt = 2;
+      if (P.fastcrt) {
         P.acc0 = 4194304;
         P.crt_sum0 = 0u - 4194304u * c32;
         P.crt_fs0 = (float)(-B);
+        P.crt_fs0d = -B;
       }
     }
   }
