@@ -112,13 +112,16 @@ def test_long_sums_with_extreme_values(C, K, moduli, xv, wv):
 @pytest.mark.parametrize("C,moduli,sign", [(49, (251, 241, 239), 1), (49, (251, 241, 239), -1),
                                            (16, (251, 241, 239), 1), (512, (65521, 65519), -1),
                                            (42, (251, 241, 239), 1), (42, (251, 241, 239), -1),
-                                           (43, (251, 241, 239), 1), (43, (251, 241, 239), -1)])
+                                           (43, (251, 241, 239), 1), (43, (251, 241, 239), -1),
+                                           (11422, (251, 241, 239, 233), 1), (11422, (251, 241, 239, 233), -1)])
 def test_results_at_the_edge_of_the_dynamic_range(C, moduli, sign):
     """All-extreme tensors drive |y| to 2^14 * 9 * C: with C = 49 and RNS(251,241,239) that is 7 225 344 of the
     7 228 674 the set can hold (section 3), so the CRT quotient is decided within 2.3e-4 of a half; C = 16 is the
     comfortable case (both precisions of the quotient estimate are exercised).  C = 42 is the largest channel count
     for which this moduli set still takes the conversion with unreduced accumulators (|y|/P = 0.428 plus twice its
-    binary32 error bound stays below 0.49), C = 43 the first that goes back to the general one."""
+    binary32 error bound stays below 0.49), C = 43 the first that takes the quotient in binary64.  C = 11422 is the
+    largest channel count four 8-bit moduli can hold (|y| = 1 684 242 432 of 1 684 281 158): there two quotients are
+    1.5e-10 apart, the tightest case of the binary64 form."""
     print("range edge", C, moduli, sign, flush=True)
     N, K, H, W, r, m, pad = 1, 16, 16, 16, 3, 8, 1
     x = np.full((N, C, H, W), -128, dtype=np.int8)
