@@ -64,9 +64,10 @@ void oracle_requant_shift_clamp(const int32_t *y, int8_t *a, size_t count, int s
 {
 #pragma omp parallel for schedule(static)
     for (size_t e = 0; e < count; ++e) {
-        int32_t v = y[e];
+        const int64_t v = y[e];
+        const int64_t d = (int64_t)1 << shift;      /* shift 0..31: 64-bit, so that 2^31 is representable */
         /* floor division by 2^shift, written without relying on >> of negatives */
-        int32_t q = v >= 0 ? v / (1 << shift) : -((-(int64_t)v + (1 << shift) - 1) / (1 << shift));
+        int64_t q = v >= 0 ? v / d : -((-v + d - 1) / d);
         if (q < -128) q = -128;
         if (q > 127) q = 127;
         a[e] = (int8_t)q;

@@ -90,6 +90,11 @@ def test_requant_is_floor_shift_and_clamp():
     assert a.tolist() == [0, 0, -1, 0, 1, -1, -2, 127, -128, 127, -128]
     rnd = (si.int8_tensor(5, (1000,)).astype(np.int32)) * 777
     assert np.array_equal(requant_shift_clamp(rnd, 6), np.clip(np.floor(rnd / 64.0), -128, 127).astype(np.int8))
+    # the ends of the shift range: shift 0 only clamps; shift 31 leaves the sign (floor(y / 2^31) is -1 or 0)
+    edge = np.array([-2 ** 31, -2 ** 31 + 1, -129, -128, -1, 0, 1, 127, 128, 2 ** 31 - 1], dtype=np.int32)
+    assert requant_shift_clamp(edge, 0).tolist() == [-128, -128, -128, -128, -1, 0, 1, 127, 127, 127]
+    assert requant_shift_clamp(edge, 31).tolist() == [-1, -1, -1, -1, -1, 0, 0, 0, 0, 0]
+    assert requant_shift_clamp(edge, 30).tolist() == [-2, -2, -1, -1, -1, 0, 0, 0, 0, 1]
 
 
 def test_maxpool():
