@@ -8,7 +8,13 @@
  * (section 6, first paragraph) is computed with F(M x M, R x R) over
  * RNS(m_0 .. m_{n-1}) (section 5, eq. "fast_algorithm_rns"; section 6, eqs.
  * "direct_sum_winograd" / "direct_sum_2" / "gemm"), and the result is
- * converted back from the residues by mixed-radix conversion (section 3).
+ * converted back from the residues (section 3, which names mixed-radix
+ * conversion or the Chinese remainder theorem for this step).  The kernels
+ * take the CRT sum with a rounded quotient,
+ *   y = sum_i (P/m_i) w_i - P rint(sum_i w_i / m_i),  w_i = Y_i (P/m_i)^-1 mod m_i,
+ * which is the same representative in [-(P-1)/2, (P-1)/2], P = prod m_i, that
+ * mixed-radix conversion with symmetric digits yields; the tests compare the
+ * two bit for bit.
  * The result is the exact integer convolution (abstract; section 9).
  *
  * In this header the paper's M, R, N = M+R-1 are spelled m, r, t; N, C, K, H, W
@@ -39,7 +45,8 @@ enum {
   RNSWINO_OK = 0,
   RNSWINO_E_INVALID = -1,              /* null pointer, non-positive size, t > 16, m < 1, output empty      */
   RNSWINO_E_UNSUPPORTED = -2,          /* stride != 1, r > 7, even modulus, modulus < 3, in 254..256 or > 65521,
-                                          8/16-bit mix, 2^14 r^2 C beyond int32, fused glue on other tile sizes */
+                                          8/16-bit mix, 2^14 r^2 C beyond int32, 16-bit moduli with C > 65472,
+                                          fused glue on other tile sizes                                     */
   RNSWINO_E_NOT_COPRIME = -3,          /* two moduli share a factor (section 3: pairwise coprime)           */
   RNSWINO_E_POINT_NOT_INVERTIBLE = -4, /* a modulus shares a factor with a difference of two interpolation
                                           points, so a denominator of V^-1 has no inverse (section 5)       */
@@ -109,7 +116,7 @@ int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, vo
 /*
  * The layer (section 6): residues of x, input transform B^T d B per tile and residue, one GEMM over C per
  * transform point and residue with the modulo after the sum, inverse transform A^T (.) A after that
- * reduction, mixed-radix conversion to int32.
+ * reduction, conversion out of the RNS to int32 (section 3; the CRT sum described at the top of this file).
  * x_dev: int8 [N][C][H][W].  U_dev: from rnswino_filter_transform.  y_dev: int32 [N][K][Ho][Wo].
  * workspace_dev: rnswino_workspace_bytes() bytes, 256-byte aligned; contents are scratch.  U_dev, workspace_dev
  * and y_dev must be 16-byte aligned (E_INVALID otherwise); x_dev may have any alignment.
@@ -165,8 +172,29 @@ int rnswino_plan_get_matrix(const rnswino_plan_t *plan, int which, int modulus_i
 #define RNSWINO_TABLE_INVERSE 1
 int64_t rnswino_plan_get_table(const rnswino_plan_t *plan, int which, int modulus_idx, int8_t *host_out, size_t capacity);
 
-/* Mixed-radix constant: inverse of moduli[l] modulo moduli[j] (l < j), in [0, moduli[j]). */
+/* Mixed-radix constant of section 3: inverse of moduli[l] modulo moduli[j] (l < j), in [0, moduli[j]).  A query for
+ * tests and for callers that convert residues themselves: no kernel reads these (the kernels use the CRT sum). */
 int rnswino_plan_get_mrc_inverse(const rnswino_plan_t *plan, int l, int j, uint32_t *host_out);
+
+/*
+ * Which kernel instantiations rnswino_conv2d (output_mode 0), or rnswino_conv2d_requant without (1) or with (2)
+ * pooling, launches for this plan, their grids, and which form of the conversion out of the RNS (section 3) the layer
+ * takes -- as text in host_out, one line per kernel in launch order, written as a profiler prints kernel names, e.g.
+ *   k1_input_transform<2, false, false> grid=200x4
+ *   k2_residue_gemm<4, 4, 2, false> grid=6400 xgroup=1
+ *   k3_inverse_crt<4, 2, false, true> grid=784x1
+ *   conversion=unreduced-binary32
+ * conversion: "unreduced-binary32" / "unreduced-binary64" = CRT sum over unreduced accumulators with the quotient rounded
+ * in that precision; "reduced-binary32" / "reduced-binary64" = over reduced residues; "reduced-binary64-mul32" = the same
+ * with full 32-bit multiplies (a partial product P/m_i of 2^24 or more).  Works on host-only plans (grids of the
+ * streaming inverse transform then assume 256 compute units).  Returns the number of bytes including the terminating
+ * zero (copied only if capacity suffices), or a negative code.  For tests and measurement scripts.
+ */
+int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, char *host_out, size_t capacity);
+
+/* Every kernel instantiation of the three hot stages the library can launch, one name per line in the form of
+ * rnswino_plan_describe (host memory; same return convention).  The tests use it to check that each is exercised. */
+int64_t rnswino_kernel_variants(char *host_out, size_t capacity);
 
 /* (prod m_i - 1)/2 saturated to 2^63-1: the largest magnitude the plan's RNS represents. */
 int64_t rnswino_plan_dynamic_range(const rnswino_plan_t *plan);

@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = (
     "rnswino_conv2d_events",
     "rnswino_requant_pool",
     "rnswino_plan_get_matrix", "rnswino_plan_get_table", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
+    "rnswino_plan_describe", "rnswino_kernel_variants",
     "rnswino_debug_stage", "rnswino_strerror",
 )
 
@@ -78,6 +79,10 @@ def lib():
         L.rnswino_plan_get_table.restype = ctypes.c_int64
         L.rnswino_plan_get_mrc_inverse.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(u32)]
         L.rnswino_plan_get_mrc_inverse.restype = ctypes.c_int
+        L.rnswino_plan_describe.argtypes = [vp, i32, ctypes.c_char_p, ctypes.c_size_t]
+        L.rnswino_plan_describe.restype = i64
+        L.rnswino_kernel_variants.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+        L.rnswino_kernel_variants.restype = i64
         L.rnswino_plan_dynamic_range.argtypes = [vp]
         L.rnswino_plan_dynamic_range.restype = i64
         L.rnswino_debug_stage.argtypes = [vp, ctypes.c_int, vp, vp]
@@ -208,6 +213,33 @@ def rnswino_plan_get_mrc_inverse(plan: Plan, l: int, j: int) -> int:
     v = ctypes.c_uint32()
     _check(lib().rnswino_plan_get_mrc_inverse(plan.handle, l, j, ctypes.byref(v)), "rnswino_plan_get_mrc_inverse")
     return v.value
+
+
+def rnswino_plan_describe(plan: Plan, output_mode: int = 0) -> dict:
+    """The library's report of what it launches for this plan: {"kernels": [names in launch order], "grids": [...],
+    "conversion": ..., "text": the raw report}."""
+    n = lib().rnswino_plan_describe(plan.handle, output_mode, None, 0)
+    _check(int(min(n, 0)), "rnswino_plan_describe")
+    buf = ctypes.create_string_buffer(int(n))
+    _check(int(min(lib().rnswino_plan_describe(plan.handle, output_mode, buf, int(n)), 0)), "rnswino_plan_describe")
+    text = buf.value.decode()
+    kernels, grids, conversion = [], [], None
+    for line in text.splitlines():
+        if line.startswith("conversion="):
+            conversion = line.split("=", 1)[1]
+        elif line:
+            name, _, rest = line.partition("> ")
+            kernels.append(name + ">")
+            grids.append(rest)
+    return {"kernels": kernels, "grids": grids, "conversion": conversion, "text": text}
+
+
+def rnswino_kernel_variants() -> list:
+    """Names of every kernel instantiation of the three hot stages the library can launch."""
+    n = int(lib().rnswino_kernel_variants(None, 0))
+    buf = ctypes.create_string_buffer(n)
+    lib().rnswino_kernel_variants(buf, n)
+    return [l for l in buf.value.decode().splitlines() if l]
 
 
 def rnswino_plan_dynamic_range(plan: Plan) -> int:

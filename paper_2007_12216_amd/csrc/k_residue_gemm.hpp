@@ -103,7 +103,8 @@ __global__ __launch_bounds__(256) void k2_residue_gemm(KParams P, const int8_t *
             }
           }
       // 8-bit residues, |U|,|V| <= 127: 512 channels add at most 8.3e6, so reducing every 8 steps keeps
-      // |acc| < 2^24.  (Byte planes need nothing here: a step adds at most 2^21 and C is below 2^14.)
+      // |acc| < 2^24.  (Byte planes need nothing here: a step adds at most 2^21 to the middle sum and the plan
+      // admits 16-bit moduli only with fewer than 1024 steps.)
       if (!WIDE && (((s0 + KS) & 7) == 0) && (s0 + KS < ncb)) {
 #pragma unroll
         for (int rm = 0; rm < RM; ++rm)

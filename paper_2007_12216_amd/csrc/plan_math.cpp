@@ -150,6 +150,10 @@ int validate_desc(const rnswino_desc_t &d, Dims &o) {
     if (p < 256) ++n8; else ++n16;
   }
   if (n8 && n16) return RNSWINO_E_UNSUPPORTED;
+  // 16-bit moduli: the GEMM keeps three unreduced 32-bit byte-plane sums over all channels; the middle one grows by up to
+  // 2 * 64 * 2^14 = 2^21 per 64-channel step, so the contraction must have fewer than 1024 steps (only 1 x 1 filters can
+  // ask for more within the int32 output bound below)
+  if (n16 && ((long long)d.C + 63) / 64 >= 1024) return RNSWINO_E_UNSUPPORTED;
   for (int i = 0; i < d.n_moduli; ++i)
     for (int j = i + 1; j < d.n_moduli; ++j)
       if (std::gcd(d.moduli[i], d.moduli[j]) != 1u) return RNSWINO_E_NOT_COPRIME;

@@ -9,8 +9,10 @@
 #include <hip/hip_ext.h>
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
+#include <string>
 #include <vector>
 
 #include "k_filter_transform.hpp"
@@ -112,161 +114,188 @@ struct Timing {
 };
 
 template <typename Kern, typename... Args>
-inline void launch(Kern kern, dim3 grid, hipStream_t st, Timing tm, Args... args) {
+inline void launch(Kern kern, dim3 grid, size_t lds, hipStream_t st, Timing tm, Args... args) {
   if (tm.start || tm.stop)
-    hipExtLaunchKernelGGL(kern, grid, dim3(256), 0, st, tm.start, tm.stop, 0, args...);
+    hipExtLaunchKernelGGL(kern, grid, dim3(256), lds, st, tm.start, tm.stop, 0, args...);
   else
-    hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, args...);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, args...);
 }
 
-// ---- K1 ----
-template <bool WIDE>
-void launch_k1(const rnswino_plan_t *plan, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm) {
-  const Dims &d = plan->dims;
+// =============================================================================================
+// Kernel selection.  Which instantiation of each kernel a layer runs, and its grid, is decided here from the plan's
+// sizes alone (no GPU needed), so that rnswino_plan_describe() can report it and the launches below cannot disagree
+// with the report.
+// =============================================================================================
+
+struct K1Choice { int KS1; bool wide, pack; unsigned gx, gy; };
+
+K1Choice choose_k1(const Dims &d) {
+  K1Choice c;
+  c.KS1 = d.KS1 < 4 ? d.KS1 : 4;
+  c.wide = d.wide != 0;
+  c.pack = d.TL > 1;
   const long long units = (long long)d.Tg * (d.Cp / 64);
   // x: multiple of 8 (see xcd_chunked()); y: one block per residue, or one block for all residues when there are
   // enough units to fill the chip (the pixel gather is then done once instead of n times; measured on the VGG16
   // stack, two blocks per CU are already enough for that to win)
-  const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)(units >= 512 ? 1 : d.n));
-  if (d.TL > 1) {
-    switch (d.KS1) {
-      case 1: launch(k1_input_transform<1, WIDE, true>, grid, st, tm, P, x, V); break;
-      case 2: launch(k1_input_transform<2, WIDE, true>, grid, st, tm, P, x, V); break;
-      case 3: launch(k1_input_transform<3, WIDE, true>, grid, st, tm, P, x, V); break;
-      default: launch(k1_input_transform<4, WIDE, true>, grid, st, tm, P, x, V); break;
-    }
-    return;
-  }
-  switch (d.KS1) {
-    case 1: launch(k1_input_transform<1, WIDE, false>, grid, st, tm, P, x, V); break;
-    case 2: launch(k1_input_transform<2, WIDE, false>, grid, st, tm, P, x, V); break;
-    case 3: launch(k1_input_transform<3, WIDE, false>, grid, st, tm, P, x, V); break;
-    default: launch(k1_input_transform<4, WIDE, false>, grid, st, tm, P, x, V); break;
-  }
+  c.gx = (unsigned)((units + 7) / 8 * 8);
+  c.gy = (unsigned)(units >= 512 ? 1 : d.n);
+  return c;
 }
 
-// ---- K2 ----
 // NTB = 16-tile column blocks per wave (1, 2 or 4, the smallest that covers Tp up to 64); KS = contraction steps
-// in flight, limited by the register budget of the variant.
-template <int KS, int NTB, int RM, bool WIDE>
-void launch_k2_one(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
+// in flight, limited by the register budget of the variant; RM = 16-row blocks per wave.
+struct K2Choice { int KS, NTB, RM; bool wide; int xgroup; unsigned blocks; };
+
+K2Choice choose_k2(const Dims &d) {
+  K2Choice c;
+  c.wide = d.wide != 0;
+  const int ntb = d.Tp / 16, ncb = d.Cp / 64;
+  c.NTB = ntb == 1 ? 1 : ntb == 2 ? 2 : 4;
+  // 64 rows per wave when K is large (V re-reads dominate), the contraction has more than one step and that still
+  // leaves >= 4 blocks per CU; measured on the VGG16 stack this wins for K >= 256 and loses for K <= 128 (8-bit
+  // moduli, full-width tiles only: the register budget of the other variants is spent on their extra accumulators)
+  const long long big_blocks = (long long)((d.n * d.Q + 7) / 8 * 8) * ((d.Kp + 63) / 64) * ((ntb + c.NTB - 1) / c.NTB);
+  if (!c.wide && c.NTB == 4 && d.Kp >= 256 && ncb >= 2 && big_blocks >= 1024) {
+    c.RM = 4;
+    c.KS = ncb % 2 == 0 ? 2 : 1;
+  } else {
+    const int ksmax = c.wide ? (c.NTB == 1 ? 4 : c.NTB == 2 ? 2 : 1) : 4;
+    c.RM = 2;
+    c.KS = (ksmax >= 4 && ncb % 4 == 0) ? 4 : (ksmax >= 2 && ncb % 2 == 0) ? 2 : 1;
+  }
   // One-dimensional grid: the kernel derives (x, row block, tile block) from the id in an order that suits the L2s.
   // A slice of U is used again after xgroup * gy workgroups of its XCD, which meanwhile touch xgroup * (U of one x +
   // about two tile-block slices of V): xgroup is the largest count for which that stays within 3 of the L2's 4 MiB.
-  const long long pl = WIDE ? 2 : 1;
-  const long long nxh = (d.n * d.Q + 7) / 8, gy = (d.Kp + 16 * RM - 1) / (16 * RM), gz = (d.Tp / 16 + NTB - 1) / NTB;
-  const long long u_x = 4LL * d.Kp * d.Cp * pl, v_slice = 4LL * 16 * NTB * d.Cp * pl;
+  const long long pl = c.wide ? 2 : 1;
+  const long long nxh = (d.n * d.Q + 7) / 8, gy = (d.Kp + 16 * c.RM - 1) / (16 * c.RM), gz = (ntb + c.NTB - 1) / c.NTB;
+  const long long u_x = 4LL * d.Kp * d.Cp * pl, v_slice = 4LL * 16 * c.NTB * d.Cp * pl;
   // With a single tile block nothing of U is used twice: one x at a time, so that the workgroups in flight on an XCD
   // read neighbouring row blocks of one U slab (measured: 3-7 % faster than walking over all x at once).
   long long xgroup = gz == 1 ? 1 : (3LL << 20) / (u_x + 2 * v_slice);
   xgroup = xgroup < 1 ? 1 : (xgroup > nxh ? nxh : xgroup);
   if (xgroup > 1 && xgroup < nxh && (xgroup & 1) == 0) --xgroup;   // measured: even group sizes run into each other in the L2 channels
-  const long long blocks = 8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz;
-  const dim3 grid((unsigned)blocks);
-  launch(k2_residue_gemm<KS, NTB, RM, WIDE>, grid, st, tm, P, U, V, O, (int)xgroup);
+  c.xgroup = (int)xgroup;
+  c.blocks = (unsigned)(8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz);
+  return c;
 }
 
-template <int NTB, bool WIDE>
-void launch_k2_ntb(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
-  const int ncb = d.Cp / 64;
-  // 64 rows per wave when K is large (V re-reads dominate), the contraction has more than one step and that still
-  // leaves >= 4 blocks per CU; measured on the
-  // VGG16 stack this wins for K >= 256 and loses for K <= 128 (8-bit moduli, full-width tiles only: the register
-  // budget of the other variants is spent on their extra accumulators)
-  const long long big_blocks = (long long)((d.n * d.Q + 7) / 8 * 8) * ((d.Kp + 63) / 64) * ((d.Tp / 16 + NTB - 1) / NTB);
-  if (!WIDE && NTB == 4 && d.Kp >= 256 && ncb >= 2 && big_blocks >= 1024) {
-    if (ncb % 2 == 0) launch_k2_one<2, NTB, (WIDE || NTB != 4) ? 2 : 4, WIDE>(d, P, U, V, O, st, tm);
-    else launch_k2_one<1, NTB, (WIDE || NTB != 4) ? 2 : 4, WIDE>(d, P, U, V, O, st, tm);
-    return;
+// stream: the streaming variant (8-bit moduli, table of all residues at most 64 KiB, n * KS3 <= 8: O operand in
+// registers twice) for layers with a unit or more per wave of the full grid (measured on the VGG16 stack);
+// fast: conversion out of the RNS from unreduced accumulators; m8: the 8 x 8 store path of the streaming variant
+// (int32 output: only with rows that keep four outputs 16-byte aligned; int8 output: only with an even row length).
+struct K3Choice { bool stream, wide, fast, m8; int NRES, KS3; unsigned gx, gy; size_t lds; };
+
+K3Choice choose_k3(const Dims &d, const KParams &P, int n_cus, int epi) {
+  K3Choice c;
+  c.wide = d.wide != 0;
+  c.NRES = d.n;
+  c.KS3 = d.KS3 < 4 ? d.KS3 : 4;
+  c.fast = !c.wide && P.fastcrt != 0;
+  c.stream = !c.wide && d.n * d.KS3 <= 8 && d.n <= 4 && d.KS3 <= 2 && (size_t)d.n * d.RB3 * d.KS3 * 1024 <= 65536 &&
+             (long long)d.Kg * (d.Tp / 16) >= 4LL * K3_STREAM_BLOCKS;
+  c.m8 = false;
+  c.lds = 0;
+  if (c.stream) {
+    const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
+    const long long max_blocks = n_cus > 0 ? 3LL * n_cus : K3_STREAM_BLOCKS;
+    c.gx = (unsigned)(blocks < max_blocks ? blocks : max_blocks);
+    c.gy = 1;
+    c.lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
+    c.m8 = c.fast && d.m == 8 && (epi == 0 ? (d.Wo & 3) == 0 : (d.Wo & 1) == 0);
+  } else {
+    const long long units = ((long long)d.Kg * d.Tg + 15) / 16;
+    c.gx = (unsigned)((units + 7) / 8 * 8);       // x multiple of 8: see xcd_chunked()
+    c.gy = (unsigned)((d.RB3 + 3) / 4);
   }
-  constexpr int KSMAX = WIDE ? (NTB == 1 ? 4 : NTB == 2 ? 2 : 1) : 4;
-  if (KSMAX >= 4 && ncb % 4 == 0) launch_k2_one<4, NTB, 2, WIDE>(d, P, U, V, O, st, tm);
-  else if (KSMAX >= 2 && ncb % 2 == 0) launch_k2_one<2, NTB, 2, WIDE>(d, P, U, V, O, st, tm);
-  else launch_k2_one<1, NTB, 2, WIDE>(d, P, U, V, O, st, tm);
+  return c;
 }
 
-template <bool WIDE>
-void launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm) {
-  const int ntb = d.Tp / 16;
-  if (ntb == 1) launch_k2_ntb<1, WIDE>(d, P, U, V, O, st, tm);
-  else if (ntb == 2) launch_k2_ntb<2, WIDE>(d, P, U, V, O, st, tm);
-  else launch_k2_ntb<4, WIDE>(d, P, U, V, O, st, tm);
+// The instantiations that exist, as tables: the launches below and rnswino_kernel_variants() both expand them.
+// Inverse transform: 16-bit moduli take the general conversion (any moduli count); with 8-bit moduli the conversion from
+// unreduced accumulators needs every P/p_i below 2^24, i.e. at most four moduli, and sets of fewer than four moduli
+// always qualify for it (their product leaves the binary64 quotient ample room), so the reduced form exists from four
+// moduli on (with exactly four, only up to t = 13: a product large enough to rule the unreduced form out needs 253,
+// which 14 or more interpolation points exclude).  The streaming kernel's 8 x 8 store path exists for the unreduced
+// form only.  A launch function returns false when the choice has no instantiation; rnswino_plan() refuses such a plan.
+#define RNSW_K1_TABLE(X) \
+  X(1, false, false) X(1, false, true) X(1, true, false) X(1, true, true) X(2, false, false) X(2, false, true) X(2, true, false) X(2, true, true) \
+  X(3, false, false) X(3, false, true) X(3, true, false) X(3, true, true) X(4, false, false) X(4, false, true) X(4, true, false) X(4, true, true)
+#define RNSW_K2_TABLE(X) \
+  X(1, 1, 2, false) X(2, 1, 2, false) X(4, 1, 2, false) X(1, 2, 2, false) X(2, 2, 2, false) X(4, 2, 2, false) \
+  X(1, 4, 2, false) X(2, 4, 2, false) X(4, 4, 2, false) X(1, 4, 4, false) X(2, 4, 4, false) \
+  X(1, 1, 2, true) X(2, 1, 2, true) X(4, 1, 2, true) X(1, 2, 2, true) X(2, 2, 2, true) X(1, 4, 2, true)
+#define RNSW_K3_NK(X, nres, wd, fs) X(nres, 1, wd, fs) X(nres, 2, wd, fs) X(nres, 3, wd, fs) X(nres, 4, wd, fs)
+#define RNSW_K3_TABLE(X) \
+  RNSW_K3_NK(X, 1, true, false) RNSW_K3_NK(X, 2, true, false) RNSW_K3_NK(X, 3, true, false) RNSW_K3_NK(X, 4, true, false) \
+  RNSW_K3_NK(X, 5, true, false) RNSW_K3_NK(X, 6, true, false) RNSW_K3_NK(X, 7, true, false) RNSW_K3_NK(X, 8, true, false) \
+  RNSW_K3_NK(X, 1, false, true) RNSW_K3_NK(X, 2, false, true) RNSW_K3_NK(X, 3, false, true) RNSW_K3_NK(X, 4, false, true) \
+  X(4, 1, false, false) X(4, 2, false, false) X(4, 3, false, false) RNSW_K3_NK(X, 5, false, false) RNSW_K3_NK(X, 6, false, false) RNSW_K3_NK(X, 7, false, false) \
+  RNSW_K3_NK(X, 8, false, false)
+#define RNSW_K3S_M8(X, nres, ks3, fs) X(nres, ks3, fs, true) X(nres, ks3, fs, false)
+#define RNSW_K3S_TABLE(X) \
+  RNSW_K3S_M8(X, 1, 1, true) RNSW_K3S_M8(X, 1, 2, true) RNSW_K3S_M8(X, 2, 1, true) RNSW_K3S_M8(X, 2, 2, true) \
+  RNSW_K3S_M8(X, 3, 1, true) RNSW_K3S_M8(X, 3, 2, true) RNSW_K3S_M8(X, 4, 1, true) RNSW_K3S_M8(X, 4, 2, true) \
+  X(4, 1, false, false) X(4, 2, false, false)
+
+// ---- K1 ----  (dry: only report whether the instantiation exists)
+bool launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipStream_t st, Timing tm, bool dry = false) {
+  const K1Choice c = choose_k1(d);
+  const dim3 grid(c.gx, c.gy);
+#define RNSW_X(ks, wd, pk) \
+  if (c.KS1 == ks && c.wide == wd && c.pack == pk) { if (!dry) launch(k1_input_transform<ks, wd, pk>, grid, 0, st, tm, P, x, V); return true; }
+  RNSW_K1_TABLE(RNSW_X)
+#undef RNSW_X
+  return false;
+}
+
+// ---- K2 ----
+bool launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm, bool dry = false) {
+  const K2Choice c = choose_k2(d);
+  const dim3 grid(c.blocks);
+#define RNSW_X(ks, ntb, rm, wd) \
+  if (c.KS == ks && c.NTB == ntb && c.RM == rm && c.wide == wd) { if (!dry) launch(k2_residue_gemm<ks, ntb, rm, wd>, grid, 0, st, tm, P, U, V, O, c.xgroup); return true; }
+  RNSW_K2_TABLE(RNSW_X)
+#undef RNSW_X
+  return false;
 }
 
 // ---- K3 ----
-template <int NRES, bool WIDE>
-void launch_k3_nres(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
-  const long long units = ((long long)d.Kg * d.Tg + 15) / 16;
-  const dim3 grid((unsigned)((units + 7) / 8 * 8), (unsigned)((d.RB3 + 3) / 4));   // x multiple of 8: see xcd_chunked()
-  if (!WIDE && P.fastcrt) {
-    switch (d.KS3) {
-      case 1: launch(k3_inverse_crt<NRES, 1, false, true>, grid, st, tm, P, O, y); break;
-      case 2: launch(k3_inverse_crt<NRES, 2, false, true>, grid, st, tm, P, O, y); break;
-      case 3: launch(k3_inverse_crt<NRES, 3, false, true>, grid, st, tm, P, O, y); break;
-      default: launch(k3_inverse_crt<NRES, 4, false, true>, grid, st, tm, P, O, y); break;
-    }
-    return;
+bool launch_k3(const Dims &d, const KParams &P, int n_cus, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm, bool dry = false) {
+  const K3Choice c = choose_k3(d, P, n_cus, P.epi);
+  const dim3 grid(c.gx, c.gy);
+  if (c.stream) {
+#define RNSW_X(nres, ks3, fs, e8) \
+    if (c.NRES == nres && c.KS3 == ks3 && c.fast == fs && c.m8 == e8) { \
+      if (!dry) launch(k3_inverse_crt_stream<nres, ks3, fs, e8>, grid, c.lds, st, tm, P, O, y); return true; }
+    RNSW_K3S_TABLE(RNSW_X)
+#undef RNSW_X
+    return false;
   }
-  switch (d.KS3) {
-    case 1: launch(k3_inverse_crt<NRES, 1, WIDE, false>, grid, st, tm, P, O, y); break;
-    case 2: launch(k3_inverse_crt<NRES, 2, WIDE, false>, grid, st, tm, P, O, y); break;
-    case 3: launch(k3_inverse_crt<NRES, 3, WIDE, false>, grid, st, tm, P, O, y); break;
-    default: launch(k3_inverse_crt<NRES, 4, WIDE, false>, grid, st, tm, P, O, y); break;
-  }
+#define RNSW_X(nres, ks3, wd, fs) \
+  if (c.NRES == nres && c.KS3 == ks3 && c.wide == wd && c.fast == fs) { \
+    if (!dry) launch(k3_inverse_crt<nres, ks3, wd, fs>, grid, 0, st, tm, P, O, y); return true; }
+  RNSW_K3_TABLE(RNSW_X)
+#undef RNSW_X
+  return false;
 }
 
-// streaming variant: 8-bit moduli, table of all residues at most 64 KiB, n * KS3 <= 8 (O operand in registers twice)
-template <int NRES, int KS3>
-void launch_k3_stream_one(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
-  const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
-  const dim3 grid((unsigned)(blocks < max_blocks ? blocks : max_blocks));
-  const size_t lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
-  // 8 x 8 tiles take their own path (int32 output: only with rows that keep four outputs 16-byte aligned; int8 output:
-  // only with an even row length)
-  const bool m8 = d.m == 8 && (P.epi == 0 ? (d.Wo & 3) == 0 : (d.Wo & 1) == 0);
-  auto kern = P.fastcrt ? (m8 ? k3_inverse_crt_stream<NRES, KS3, true, true> : k3_inverse_crt_stream<NRES, KS3, true, false>)
-                        : (m8 ? k3_inverse_crt_stream<NRES, KS3, false, true> : k3_inverse_crt_stream<NRES, KS3, false, false>);
-  if (tm.start || tm.stop)
-    hipExtLaunchKernelGGL(kern, grid, dim3(256), lds, st, tm.start, tm.stop, 0, P, O, y);
-  else
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, P, O, y);
-}
-
-inline bool k3_stream_applies(const Dims &d) {
-  return !d.wide && d.n * d.KS3 <= 8 && d.n <= 4 && d.KS3 <= 2 && (size_t)d.n * d.RB3 * d.KS3 * 1024 <= 65536 &&
-         (long long)d.Kg * (d.Tp / 16) >= 4LL * K3_STREAM_BLOCKS;   // a unit or more per wave of the full grid (measured on the VGG16 stack)
-}
-
-void launch_k3_stream(const Dims &d, const KParams &P, const uint32_t *O, int32_t *y, int max_blocks, hipStream_t st, Timing tm) {
-  switch (d.n * 10 + d.KS3) {
-    case 11: launch_k3_stream_one<1, 1>(d, P, O, y, max_blocks, st, tm); break;
-    case 12: launch_k3_stream_one<1, 2>(d, P, O, y, max_blocks, st, tm); break;
-    case 21: launch_k3_stream_one<2, 1>(d, P, O, y, max_blocks, st, tm); break;
-    case 22: launch_k3_stream_one<2, 2>(d, P, O, y, max_blocks, st, tm); break;
-    case 31: launch_k3_stream_one<3, 1>(d, P, O, y, max_blocks, st, tm); break;
-    case 32: launch_k3_stream_one<3, 2>(d, P, O, y, max_blocks, st, tm); break;
-    case 41: launch_k3_stream_one<4, 1>(d, P, O, y, max_blocks, st, tm); break;
-    default: launch_k3_stream_one<4, 2>(d, P, O, y, max_blocks, st, tm); break;
-  }
-}
-
-template <bool WIDE>
-void launch_k3(const rnswino_plan_t *plan, const KParams &P, const uint32_t *O, int32_t *y, hipStream_t st, Timing tm) {
-  const Dims &d = plan->dims;
-  if (!WIDE && k3_stream_applies(d)) {   // many units: table in LDS, waves stream over the units
-    launch_k3_stream(d, P, O, y, plan->n_cus > 0 ? 3 * plan->n_cus : K3_STREAM_BLOCKS, st, tm);
-    return;
-  }
-  switch (d.n) {
-    case 1: launch_k3_nres<1, WIDE>(d, P, O, y, st, tm); break;
-    case 2: launch_k3_nres<2, WIDE>(d, P, O, y, st, tm); break;
-    case 3: launch_k3_nres<3, WIDE>(d, P, O, y, st, tm); break;
-    case 4: launch_k3_nres<4, WIDE>(d, P, O, y, st, tm); break;
-    case 5: launch_k3_nres<5, WIDE>(d, P, O, y, st, tm); break;
-    case 6: launch_k3_nres<6, WIDE>(d, P, O, y, st, tm); break;
-    case 7: launch_k3_nres<7, WIDE>(d, P, O, y, st, tm); break;
-    default: launch_k3_nres<8, WIDE>(d, P, O, y, st, tm); break;
-  }
+// Every name of the tables above, one per line, as a profiler prints them.
+std::string all_kernel_variants() {
+  std::string out;
+#define RNSW_X(ks, wd, pk) out += "k1_input_transform<" #ks ", " #wd ", " #pk ">\n";
+  RNSW_K1_TABLE(RNSW_X)
+#undef RNSW_X
+#define RNSW_X(ks, ntb, rm, wd) out += "k2_residue_gemm<" #ks ", " #ntb ", " #rm ", " #wd ">\n";
+  RNSW_K2_TABLE(RNSW_X)
+#undef RNSW_X
+#define RNSW_X(nres, ks3, wd, fs) out += "k3_inverse_crt<" #nres ", " #ks3 ", " #wd ", " #fs ">\n";
+  RNSW_K3_TABLE(RNSW_X)
+#undef RNSW_X
+#define RNSW_X(nres, ks3, fs, m8) out += "k3_inverse_crt_stream<" #nres ", " #ks3 ", " #fs ", " #m8 ">\n";
+  RNSW_K3S_TABLE(RNSW_X)
+#undef RNSW_X
+  return out;
 }
 
 // epi: 0 = int32 y_dev; 1 / 2 = int8 act_dev after shift/clamp (/ and 2x2 max-pool)
@@ -291,9 +320,10 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
     t2.start = (hipEvent_t)events[2]; t2.stop = (hipEvent_t)events[3];
     t3.start = (hipEvent_t)events[4]; t3.stop = (hipEvent_t)events[5];
   }
-  if (d.wide) launch_k1<true>(plan, P, x_dev, Vp, st, t1); else launch_k1<false>(plan, P, x_dev, Vp, st, t1);
-  if (d.wide) launch_k2<true>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2); else launch_k2<false>(d, P, (const int8_t *)U_dev, Vp, Op, st, t2);
-  if (d.wide) launch_k3<true>(plan, P, Op, y_dev, st, t3); else launch_k3<false>(plan, P, Op, y_dev, st, t3);
+  // (rnswino_plan() has checked that all three instantiations exist)
+  if (!launch_k1(d, P, x_dev, Vp, st, t1) || !launch_k2(d, P, (const int8_t *)U_dev, Vp, Op, st, t2) ||
+      !launch_k3(d, P, plan->n_cus, Op, y_dev, st, t3))
+    return RNSWINO_E_UNSUPPORTED;
   return launch_status();
 }
 
@@ -354,6 +384,16 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   }
   pl->kparams = new (std::nothrow) KParams(make_params(pl));
   if (!pl->kparams) { (void)rnswino_plan_destroy(pl); return RNSWINO_E_INVALID; }
+  {
+    // every kernel the layer would launch, in each output mode, must be an instantiation that exists
+    KParams P = *(const KParams *)pl->kparams;
+    bool ok = launch_k1(d, P, nullptr, nullptr, nullptr, Timing(), true) && launch_k2(d, P, nullptr, nullptr, nullptr, nullptr, Timing(), true);
+    for (int epi = 0; epi < 3 && ok; ++epi) {
+      P.epi = epi;
+      ok = launch_k3(d, P, pl->n_cus, nullptr, nullptr, nullptr, Timing(), true);
+    }
+    if (!ok) { (void)rnswino_plan_destroy(pl); return RNSWINO_E_UNSUPPORTED; }
+  }
   *out = pl;
   return RNSWINO_OK;
 }
@@ -412,6 +452,38 @@ int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const
                           void *workspace_dev, void *stream, void *const events[6]) {
   if (!events) return RNSWINO_E_INVALID;
   return conv2d_impl(plan, x_dev, U_dev, y_dev, workspace_dev, stream, events);
+}
+
+int64_t rnswino_kernel_variants(char *host_out, size_t capacity) {
+  const std::string all = all_kernel_variants();
+  if (host_out && capacity > all.size()) std::memcpy(host_out, all.c_str(), all.size() + 1);
+  return (int64_t)all.size() + 1;
+}
+
+int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, char *host_out, size_t capacity) {
+  if (!plan || output_mode < 0 || output_mode > 2) return RNSWINO_E_INVALID;
+  const Dims &d = plan->dims;
+  const KParams &P = *(const KParams *)plan->kparams;
+  const K1Choice c1 = choose_k1(d);
+  const K2Choice c2 = choose_k2(d);
+  const K3Choice c3 = choose_k3(d, P, plan->n_cus, output_mode);
+  auto tf = [](bool b) { return b ? "true" : "false"; };
+  char buf[1024];
+  int len = std::snprintf(buf, sizeof(buf), "k1_input_transform<%d, %s, %s> grid=%ux%u\nk2_residue_gemm<%d, %d, %d, %s> grid=%u xgroup=%d\n",
+                          c1.KS1, tf(c1.wide), tf(c1.pack), c1.gx, c1.gy, c2.KS, c2.NTB, c2.RM, tf(c2.wide), c2.blocks, c2.xgroup);
+  if (c3.stream)
+    len += std::snprintf(buf + len, sizeof(buf) - len, "k3_inverse_crt_stream<%d, %d, %s, %s> grid=%ux%u lds=%zu\n", c3.NRES, c3.KS3,
+                         tf(c3.fast), tf(c3.m8), c3.gx, c3.gy, c3.lds);
+  else
+    len += std::snprintf(buf + len, sizeof(buf) - len, "k3_inverse_crt<%d, %d, %s, %s> grid=%ux%u\n", c3.NRES, c3.KS3, tf(c3.wide),
+                         tf(c3.fast), c3.gx, c3.gy);
+  const char *conv = P.fastcrt == 1 ? "unreduced-binary32"
+                     : P.fastcrt == 2 ? "unreduced-binary64"
+                     : !P.crt24 ? "reduced-binary64-mul32"
+                     : P.quot32 ? "reduced-binary32" : "reduced-binary64";
+  len += std::snprintf(buf + len, sizeof(buf) - len, "conversion=%s\n", conv);
+  if (host_out && capacity > (size_t)len) std::memcpy(host_out, buf, (size_t)len + 1);
+  return (int64_t)len + 1;
 }
 
 int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, int32_t H, int32_t W, int32_t shift,

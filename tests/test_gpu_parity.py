@@ -8,6 +8,8 @@ import paper_2007_12216_amd as rn
 from oracle import direct_conv2d
 from oracle import rnswino as rw
 
+import variant_cases as vc
+
 pytestmark = pytest.mark.gpu
 
 
@@ -465,3 +467,88 @@ def test_the_papers_vgg16_setting_with_a_trusted_range():
     assert np.abs(ref.astype(np.int64)).max() <= (251 * 241 * 239 - 1) // 2
     _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w, flags=rn.FLAG_ALLOW_UNCHECKED_RANGE)
     assert np.array_equal(y, ref)
+
+
+@pytest.mark.parametrize("entry", vc.select_cases(), ids=[vc.case_id(e) for e in vc.select_cases()])
+def test_every_kernel_variant(entry):
+    """Layers chosen (tests/variant_cases.py) so that every instantiation of the three kernels the library can launch, every
+    form of the conversion out of the RNS and every output mode of the streaming inverse transform runs at least once:
+    each against the direct-convolution oracle (reduced to the symmetric range of the moduli set where the range was left
+    unchecked and is exceeded), for the int8 output modes followed by the oracle's shift/clamp and max-pool."""
+    from oracle import requant_shift_clamp, maxpool2x2
+    from paper_2007_12216_amd.layer import ConvLayer
+    (N, C, K, H, W, r, m, pad, moduli, flags, mode), kernels, conversion = entry
+    print("variant case", vc.case_id(entry), kernels, conversion, flush=True)
+    x = si.int8_tensor(601, (N, C, H, W))
+    w = si.int8_tensor(602, (K, C, r, r))
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, flags)
+    d = rn.rnswino_plan_describe(layer.plan, mode)
+    assert tuple(d["kernels"]) == kernels and d["conversion"] == conversion
+    layer.set_weights(w)
+    P = 1
+    for p in moduli:
+        P *= int(p)
+    ref = direct_conv2d(x, w, pad)
+    if flags & rn.FLAG_ALLOW_UNCHECKED_RANGE:
+        ref = rw.sym(ref.astype(np.int64), P).astype(np.int32)
+    xd = torch.from_numpy(x).to("cuda:0")
+    if mode == 0:
+        y = layer.forward(xd)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), ref)
+        return
+    shift = max(0, int(round(np.log2(74.0 * np.sqrt(float(r * r * C))))) - (0 if P > 1 << 24 else 8))
+    Ho, Wo = layer.plan.Ho, layer.plan.Wo
+    a = torch.empty((N, K, Ho // 2, Wo // 2) if mode == 2 else (N, K, Ho, Wo), dtype=torch.int8, device="cuda:0")
+    rn.rnswino_conv2d_requant(layer.plan, xd, layer.U, a, shift, mode == 2, layer.workspace, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = requant_shift_clamp(ref, shift)
+    if mode == 2:
+        want = maxpool2x2(want)
+    assert np.array_equal(a.cpu().numpy(), want)
+
+
+def test_the_event_taking_entry_point_computes_the_same_output():
+    """rnswino_conv2d_events is rnswino_conv2d with timestamps: same output, and six usable events."""
+    import ctypes
+    from paper_2007_12216_amd.layer import ConvLayer
+    print("events entry", flush=True)
+    cfg = si.layer_config(3)
+    x, w = si.layer_tensors(cfg)
+    layer = ConvLayer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["r"], cfg["m"], cfg["pad"], cfg["moduli"])
+    layer.set_weights(w)
+    xd = torch.from_numpy(x).to("cuda:0")
+    y_plain = layer.forward(xd).clone()
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    events = []
+    for _ in range(6):
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        events.append(e.value)
+    y_ev = torch.zeros_like(layer.y)
+    rn.rnswino_conv2d_events(layer.plan, xd, layer.U, y_ev, layer.workspace, torch.cuda.current_stream().cuda_stream, events)
+    torch.cuda.synchronize()
+    assert torch.equal(y_ev, y_plain)
+    assert np.array_equal(y_ev.cpu().numpy(), direct_conv2d(x, w, cfg["pad"]))
+    for j in range(3):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), events[2 * j], events[2 * j + 1]) == 0
+        assert 0.0 < ms.value < 100.0
+    for e in events:
+        hip.hipEventDestroy(e)
+
+
+def test_requant_pool_at_the_ends_of_the_shift_range():
+    """Shift 0 (clamp only, negative values included) and shift 31 (only the sign survives) of the stand-alone glue kernel."""
+    from oracle import requant_shift_clamp
+    print("requant shift range", flush=True)
+    y = np.array([[-2 ** 31, -2 ** 31 + 1, -129, -128, -1, 0, 1, 127, 128, 2 ** 31 - 1, 12345, -54321]], dtype=np.int32).reshape(1, 1, 2, 6)
+    yd = torch.from_numpy(y).to("cuda:0")
+    for shift in (0, 1, 30, 31):
+        a = torch.empty(y.shape, dtype=torch.int8, device="cuda:0")
+        rn.rnswino_requant_pool(yd, a, 1, 2, 6, shift, False, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(a.cpu().numpy(), requant_shift_clamp(y, shift)), shift
