@@ -53,7 +53,9 @@ enum {
   RNSWINO_E_RANGE = -5,                /* 2^14 r^2 C exceeds (prod m_i - 1)/2: the dynamic range of the RNS
                                           cannot hold the worst-case output (sections 3, 5, 8)              */
   RNSWINO_E_HIP = -6,                  /* a HIP runtime call or kernel launch failed                        */
-  RNSWINO_E_NO_DEVICE = -7             /* the plan was made host-only, or no GPU is present                 */
+  RNSWINO_E_NO_DEVICE = -7,            /* the plan was made host-only, or no GPU is present                 */
+  RNSWINO_E_WORKSPACE = -8             /* rnswino_conv2d_static: the layer needs more workspace than
+                                          RNSWINO_STATIC_WORKSPACE_BYTES                                    */
 };
 
 enum {
@@ -126,6 +128,22 @@ int rnswino_filter_transform(const rnswino_plan_t *plan, const int8_t *w_dev, vo
  */
 int rnswino_conv2d(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev,
                    int32_t *y_dev, void *workspace_dev, void *stream);
+
+/*
+ * rnswino_conv2d for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation and same kernels; the transformed
+ * input V and the GEMM output O live in a buffer of RNSWINO_STATIC_WORKSPACE_BYTES that is part of the library's loaded
+ * code object on each GPU (held until the process ends; its per-device address is looked up once, when the first plan is
+ * made on that device).  The call allocates and frees nothing and does not synchronise.  Layers whose
+ * rnswino_workspace_bytes() exceeds the buffer are refused with RNSWINO_E_WORKSPACE (nothing is launched).
+ * Every call on a GPU uses that GPU's one buffer: calls that may overlap in time (different streams without an event
+ * between them, or different host threads) race; calls on one stream are ordered and safe.  The buffer keeps the last
+ * call's contents; nothing in it needs clearing: the only bytes a call reads before it has written them belong to padding
+ * tiles, whose results are never stored.
+ * x_dev, U_dev, y_dev: as for rnswino_conv2d.
+ */
+#define RNSWINO_STATIC_WORKSPACE_BYTES (16u << 20)
+int rnswino_conv2d_static(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev, void *stream);
 
 /*
  * rnswino_conv2d fused with the layer glue of rnswino_requant_pool: the inverse-transform kernel writes

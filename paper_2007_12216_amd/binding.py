@@ -16,7 +16,7 @@ FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY = 1, 2
 EXPORTED_SYMBOLS = (
     "rnswino_plan", "rnswino_plan_destroy", "rnswino_output_dims", "rnswino_filter_bytes",
     "rnswino_workspace_bytes", "rnswino_filter_transform", "rnswino_conv2d", "rnswino_conv2d_requant",
-    "rnswino_conv2d_events",
+    "rnswino_conv2d_events", "rnswino_conv2d_static",
     "rnswino_requant_pool",
     "rnswino_plan_get_matrix", "rnswino_plan_get_table", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
     "rnswino_plan_describe", "rnswino_kernel_variants",
@@ -71,6 +71,8 @@ def lib():
         L.rnswino_conv2d_requant.restype = ctypes.c_int
         L.rnswino_conv2d_events.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
         L.rnswino_conv2d_events.restype = ctypes.c_int
+        L.rnswino_conv2d_static.argtypes = [vp, vp, vp, vp, vp]
+        L.rnswino_conv2d_static.restype = ctypes.c_int
         L.rnswino_requant_pool.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp]
         L.rnswino_requant_pool.restype = ctypes.c_int
         L.rnswino_plan_get_matrix.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
@@ -182,6 +184,13 @@ def rnswino_conv2d_events(plan: Plan, x_dev, U_dev, y_dev, workspace_dev, stream
     arr = (ctypes.c_void_p * 6)(*[int(e) for e in events])
     _check(lib().rnswino_conv2d_events(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev), _ptr(workspace_dev), stream, arr),
            "rnswino_conv2d_events")
+
+
+STATIC_WORKSPACE_BYTES = 16 << 20
+
+
+def rnswino_conv2d_static(plan: Plan, x_dev, U_dev, y_dev, stream: int = 0) -> None:
+    _check(lib().rnswino_conv2d_static(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev), stream), "rnswino_conv2d_static")
 
 
 def rnswino_requant_pool(y_dev, a_dev, planes: int, H: int, W: int, shift: int, pool: bool, stream: int = 0) -> None:

@@ -11,6 +11,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -26,7 +27,28 @@
 
 using namespace rnswino;
 
+// Workspace of rnswino_conv2d_static(): device memory that is part of the loaded code object, so the entry point needs
+// no allocation.  Every GPU holds its own copy at its own address; in host code the name below is only a handle for
+// hipGetSymbolAddress(), never an address to hand to a kernel.
+static __device__ __align__(256) unsigned char scratch[RNSWINO_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+// Address of `scratch` on each device, looked up once per device (with that device current) when the first plan is
+// made there; rnswino_conv2d_static() only reads it.
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES] = {};
+
+int resolve_scratch(int dev) {          // called with device `dev` current
+  if (dev < 0 || dev >= MAX_DEVICES) return RNSWINO_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_ptr[dev]) return RNSWINO_OK;
+  void *ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return RNSWINO_E_HIP; }
+  scratch_ptr[dev] = ptr;
+  return RNSWINO_OK;
+}
 
 KParams make_params(const rnswino_plan_t *pl) {
   KParams P;
@@ -376,6 +398,8 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
       (void)hipGetLastError(); (void)hipFree(pl->d_tables); delete pl; return RNSWINO_E_HIP;
     }
     pl->device = dev;
+    rc = resolve_scratch(dev);
+    if (rc != RNSWINO_OK) { (void)hipFree(pl->d_tables); delete pl; return rc; }
     {
       int cus = 0;
       if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) pl->n_cus = cus;
@@ -458,6 +482,15 @@ int64_t rnswino_kernel_variants(char *host_out, size_t capacity) {
   const std::string all = all_kernel_variants();
   if (host_out && capacity > all.size()) std::memcpy(host_out, all.c_str(), all.size() + 1);
   return (int64_t)all.size() + 1;
+}
+
+int rnswino_conv2d_static(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_dev, int32_t *y_dev, void *stream) {
+  if (!plan) return RNSWINO_E_INVALID;
+  if (plan->device < 0) return RNSWINO_E_NO_DEVICE;
+  if (rnswino_workspace_bytes(plan) > (size_t)RNSWINO_STATIC_WORKSPACE_BYTES) return RNSWINO_E_WORKSPACE;
+  void *ws = plan->device < MAX_DEVICES ? scratch_ptr[plan->device] : nullptr;   // set when the plan was made
+  if (!ws) return RNSWINO_E_HIP;
+  return conv2d_impl(plan, x_dev, U_dev, y_dev, ws, stream, nullptr);
 }
 
 int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, char *host_out, size_t capacity) {
@@ -593,6 +626,7 @@ const char *rnswino_strerror(int code) {
     case RNSWINO_E_RANGE: return "dynamic range of the moduli set is below the worst-case output 2^14 r^2 C";
     case RNSWINO_E_HIP: return "HIP runtime error";
     case RNSWINO_E_NO_DEVICE: return "plan is host-only or no GPU is available";
+    case RNSWINO_E_WORKSPACE: return "the layer needs more workspace than the library's static buffer holds";
     default: return "unknown error";
   }
 }
