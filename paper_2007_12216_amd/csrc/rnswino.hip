@@ -21,6 +21,7 @@
 #include "k_input_transform.hpp"
 #include "k_inverse_crt.hpp"
 #include "k_residue_gemm.hpp"
+#include "k_residue_gemm_lds.hpp"
 #include "layout.hpp"
 #include "plan.hpp"
 #include "rnswino.h"
@@ -167,13 +168,43 @@ K1Choice choose_k1(const Dims &d) {
 
 // NTB = 16-tile column blocks per wave (1, 2 or 4, the smallest that covers Tp up to 64); KS = contraction steps
 // in flight, limited by the register budget of the variant; RM = 16-row blocks per wave.
-struct K2Choice { int KS, NTB, RM; bool wide; int xgroup; unsigned blocks; };
+// lds: the LDS-tiled kernel (8-bit moduli): WM x WN waves of RM x NTB fragments each, S steps in flight.
+struct K2Choice { int KS, NTB, RM; bool wide; int xgroup; unsigned blocks; bool lds; int WM, WN, S; };
+
+// L2-aware grouping of the x index (see the kernels): brf / btf = row / tile fragments per workgroup
+void k2_grid(const Dims &d, int brf, int btf, K2Choice &c) {
+  const int ntb = d.Tp / 16;
+  const long long pl = c.wide ? 2 : 1;
+  const long long nxh = (d.n * d.Q + 7) / 8, gy = (d.Kp / 16 + brf - 1) / brf, gz = (ntb + btf - 1) / btf;
+  const long long u_x = 4LL * d.Kp * d.Cp * pl, v_slice = 4LL * 16 * btf * d.Cp * pl;
+  long long xgroup = gz == 1 ? 1 : (3LL << 20) / (u_x + 2 * v_slice);
+  xgroup = xgroup < 1 ? 1 : (xgroup > nxh ? nxh : xgroup);
+  if (xgroup > 1 && xgroup < nxh && (xgroup & 1) == 0) --xgroup;
+  c.xgroup = (int)xgroup;
+  c.blocks = (unsigned)(8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz);
+}
 
 K2Choice choose_k2(const Dims &d) {
   K2Choice c;
   c.wide = d.wide != 0;
+  c.lds = false; c.WM = c.WN = c.S = 0;
   const int ntb = d.Tp / 16, ncb = d.Cp / 64;
   c.NTB = ntb == 1 ? 1 : ntb == 2 ? 2 : 4;
+  if (!c.wide && d.Kp >= 128) {
+    // LDS-tiled kernel where it measured faster than the register-direct one (VGG16 stack at batch 8, the 256-channel
+    // layer at batch 1): 128 x 64 blocks for 33..64 tiles; 128 x 128 blocks for many tiles, unless the last tile block
+    // would be mostly padding (more than a tenth of the tile blocks wasted) on a contraction of several steps
+    const int tb128 = (ntb + 7) / 8;
+    const bool few = ntb == 3 || ntb == 4;
+    const bool many = ntb >= 5 && (ncb == 1 || tb128 * 80 <= ntb * 11);
+    if (few || many) {
+      c.lds = true; c.KS = 0; c.NTB = 4;
+      if (few) { c.WM = 4; c.WN = 1; c.RM = 2; c.S = 4; }
+      else { c.WM = 2; c.WN = 2; c.RM = 4; c.S = 3; }
+      k2_grid(d, c.WM * c.RM, c.WN * c.NTB, c);
+      return c;
+    }
+  }
   // 64 rows per wave when K is large (V re-reads dominate), the contraction has more than one step and that still
   // leaves >= 4 blocks per CU; measured on the VGG16 stack this wins for K >= 256 and loses for K <= 128 (8-bit
   // moduli, full-width tiles only: the register budget of the other variants is spent on their extra accumulators)
@@ -189,16 +220,10 @@ K2Choice choose_k2(const Dims &d) {
   // One-dimensional grid: the kernel derives (x, row block, tile block) from the id in an order that suits the L2s.
   // A slice of U is used again after xgroup * gy workgroups of its XCD, which meanwhile touch xgroup * (U of one x +
   // about two tile-block slices of V): xgroup is the largest count for which that stays within 3 of the L2's 4 MiB.
-  const long long pl = c.wide ? 2 : 1;
-  const long long nxh = (d.n * d.Q + 7) / 8, gy = (d.Kp + 16 * c.RM - 1) / (16 * c.RM), gz = (ntb + c.NTB - 1) / c.NTB;
-  const long long u_x = 4LL * d.Kp * d.Cp * pl, v_slice = 4LL * 16 * c.NTB * d.Cp * pl;
   // With a single tile block nothing of U is used twice: one x at a time, so that the workgroups in flight on an XCD
-  // read neighbouring row blocks of one U slab (measured: 3-7 % faster than walking over all x at once).
-  long long xgroup = gz == 1 ? 1 : (3LL << 20) / (u_x + 2 * v_slice);
-  xgroup = xgroup < 1 ? 1 : (xgroup > nxh ? nxh : xgroup);
-  if (xgroup > 1 && xgroup < nxh && (xgroup & 1) == 0) --xgroup;   // measured: even group sizes run into each other in the L2 channels
-  c.xgroup = (int)xgroup;
-  c.blocks = (unsigned)(8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz);
+  // read neighbouring row blocks of one U slab (measured: 3-7 % faster than walking over all x at once).  Even group
+  // sizes measured slower (they run into each other in the L2 channels).
+  k2_grid(d, c.RM, c.NTB, c);
   return c;
 }
 
@@ -247,6 +272,7 @@ K3Choice choose_k3(const Dims &d, const KParams &P, int n_cus, int epi) {
   X(1, 1, 2, false) X(2, 1, 2, false) X(4, 1, 2, false) X(1, 2, 2, false) X(2, 2, 2, false) X(4, 2, 2, false) \
   X(1, 4, 2, false) X(2, 4, 2, false) X(4, 4, 2, false) X(1, 4, 4, false) X(2, 4, 4, false) \
   X(1, 1, 2, true) X(2, 1, 2, true) X(4, 1, 2, true) X(1, 2, 2, true) X(2, 2, 2, true) X(1, 4, 2, true)
+#define RNSW_K2L_TABLE(X) X(2, 2, 4, 4, 3) X(4, 1, 2, 4, 4)
 #define RNSW_K3_NK(X, nres, wd, fs) X(nres, 1, wd, fs) X(nres, 2, wd, fs) X(nres, 3, wd, fs) X(nres, 4, wd, fs)
 #define RNSW_K3_TABLE(X) \
   RNSW_K3_NK(X, 1, true, false) RNSW_K3_NK(X, 2, true, false) RNSW_K3_NK(X, 3, true, false) RNSW_K3_NK(X, 4, true, false) \
@@ -275,6 +301,14 @@ bool launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipS
 bool launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm, bool dry = false) {
   const K2Choice c = choose_k2(d);
   const dim3 grid(c.blocks);
+  if (c.lds) {
+#define RNSW_X(wm_, wn_, rm, ntb, s_) \
+    if (c.WM == wm_ && c.WN == wn_ && c.RM == rm && c.NTB == ntb && c.S == s_) { \
+      if (!dry) launch(k2_residue_gemm_lds<wm_, wn_, rm, ntb, s_>, grid, 0, st, tm, P, U, V, O, c.xgroup); return true; }
+    RNSW_K2L_TABLE(RNSW_X)
+#undef RNSW_X
+    return false;
+  }
 #define RNSW_X(ks, ntb, rm, wd) \
   if (c.KS == ks && c.NTB == ntb && c.RM == rm && c.wide == wd) { if (!dry) launch(k2_residue_gemm<ks, ntb, rm, wd>, grid, 0, st, tm, P, U, V, O, c.xgroup); return true; }
   RNSW_K2_TABLE(RNSW_X)
@@ -310,6 +344,9 @@ std::string all_kernel_variants() {
 #undef RNSW_X
 #define RNSW_X(ks, ntb, rm, wd) out += "k2_residue_gemm<" #ks ", " #ntb ", " #rm ", " #wd ">\n";
   RNSW_K2_TABLE(RNSW_X)
+#undef RNSW_X
+#define RNSW_X(wm_, wn_, rm, ntb, s_) out += "k2_residue_gemm_lds<" #wm_ ", " #wn_ ", " #rm ", " #ntb ", " #s_ ">\n";
+  RNSW_K2L_TABLE(RNSW_X)
 #undef RNSW_X
 #define RNSW_X(nres, ks3, wd, fs) out += "k3_inverse_crt<" #nres ", " #ks3 ", " #wd ", " #fs ">\n";
   RNSW_K3_TABLE(RNSW_X)
@@ -502,8 +539,13 @@ int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, c
   const K3Choice c3 = choose_k3(d, P, plan->n_cus, output_mode);
   auto tf = [](bool b) { return b ? "true" : "false"; };
   char buf[1024];
-  int len = std::snprintf(buf, sizeof(buf), "k1_input_transform<%d, %s, %s> grid=%ux%u\nk2_residue_gemm<%d, %d, %d, %s> grid=%u xgroup=%d\n",
-                          c1.KS1, tf(c1.wide), tf(c1.pack), c1.gx, c1.gy, c2.KS, c2.NTB, c2.RM, tf(c2.wide), c2.blocks, c2.xgroup);
+  int len = std::snprintf(buf, sizeof(buf), "k1_input_transform<%d, %s, %s> grid=%ux%u\n", c1.KS1, tf(c1.wide), tf(c1.pack), c1.gx, c1.gy);
+  if (c2.lds)
+    len += std::snprintf(buf + len, sizeof(buf) - len, "k2_residue_gemm_lds<%d, %d, %d, %d, %d> grid=%u xgroup=%d\n", c2.WM, c2.WN, c2.RM,
+                         c2.NTB, c2.S, c2.blocks, c2.xgroup);
+  else
+    len += std::snprintf(buf + len, sizeof(buf) - len, "k2_residue_gemm<%d, %d, %d, %s> grid=%u xgroup=%d\n", c2.KS, c2.NTB, c2.RM,
+                         tf(c2.wide), c2.blocks, c2.xgroup);
   if (c3.stream)
     len += std::snprintf(buf + len, sizeof(buf) - len, "k3_inverse_crt_stream<%d, %d, %s, %s> grid=%ux%u lds=%zu\n", c3.NRES, c3.KS3,
                          tf(c3.fast), tf(c3.m8), c3.gx, c3.gy, c3.lds);

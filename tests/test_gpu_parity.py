@@ -69,6 +69,11 @@ SHAPE_CASES = [
     (1, 32, 48, 28, 28, 3, 14, 1, (65521, 65519)),
     (2, 20, 20, 11, 11, 3, 6, 1, (251, 241, 239)),           # F(6x6,3x3), odd t*t? t = 8
     (1, 8, 8, 9, 9, 3, 7, 1, (251, 241, 239)),               # t = 9: 81 transform points, ragged group of four
+    # LDS-tiled GEMM (128 and more rows, three and more tile blocks): contractions longer than its pipeline, ragged blocks
+    (1, 1100, 130, 40, 40, 3, 6, 1, (251, 241, 239, 233)),   # 18 steps with a reduction in between, 49 tiles, ragged rows
+    (1, 256, 200, 64, 64, 3, 6, 1, (251, 241, 239, 233)),    # 128 x 128 blocks: 121 tiles, 200 rows
+    (2, 70, 136, 44, 44, 3, 7, 1, (251, 241, 239, 233)),     # 81 points: last point group holds one; 98 tiles
+    (1, 192, 128, 96, 96, 3, 8, 1, (251, 241, 239, 233)),    # 144 tiles = two 128-tile blocks, the second mostly padding
 ]
 
 
@@ -94,15 +99,17 @@ def test_extreme_values(xv, wv):
     assert abs(int(ref[0, 0, 5, 5])) == abs(xv * wv) * 9 * C
 
 
-@pytest.mark.parametrize("C,K,moduli,xv,wv", [(2100, 16, (251, 241, 239, 233), -128, -128),
-                                              (2100, 16, (251, 241, 239, 233), -128, 127),
-                                              (2100, 16, (65521, 65519), -128, -128),
-                                              (70, 1030, (251, 241, 239, 233), 127, -128)])
-def test_long_sums_with_extreme_values(C, K, moduli, xv, wv):
+@pytest.mark.parametrize("C,K,moduli,xv,wv,hw", [(2100, 16, (251, 241, 239, 233), -128, -128, 8),
+                                                 (2100, 16, (251, 241, 239, 233), -128, 127, 8),
+                                                 (2100, 16, (65521, 65519), -128, -128, 8),
+                                                 (70, 1030, (251, 241, 239, 233), 127, -128, 8),
+                                                 (2100, 128, (251, 241, 239, 233), -128, -128, 36),
+                                                 (2100, 128, (251, 241, 239, 233), -128, 127, 36)])
+def test_long_sums_with_extreme_values(C, K, moduli, xv, wv, hw):
     """Accumulator headroom of the GEMM (reduced every 512 channels for 8-bit moduli, three byte-plane accumulators for
     16-bit ones) with every product at its largest magnitude, and a K that leaves a ragged last row block."""
     print("long sums", C, K, moduli, xv, wv, flush=True)
-    N, H, W, r, m, pad = 1, 8, 8, 3, 6, 1
+    N, H, W, r, m, pad = 1, hw, hw, 3, 6, 1                     # hw = 36: 36 tiles, the LDS-tiled GEMM
     x = np.full((N, C, H, W), xv, dtype=np.int8)
     w = np.full((K, C, r, r), wv, dtype=np.int8)
     _, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)

@@ -62,7 +62,7 @@ def test_workload_kernels():
     """The instantiations the five benchmark workloads launch (the names a kernel trace of bench.py shows)."""
     import synth_inputs as si
     want = {1: ("k1_input_transform<2, false, false>", "k2_residue_gemm<1, 1, 2, false>", "k3_inverse_crt<3, 2, false, true>"),
-            2: ("k1_input_transform<2, false, false>", "k2_residue_gemm<4, 4, 2, false>", "k3_inverse_crt<4, 2, false, true>"),
+            2: ("k1_input_transform<2, false, false>", "k2_residue_gemm_lds<4, 1, 2, 4, 4>", "k3_inverse_crt<4, 2, false, true>"),
             3: ("k1_input_transform<4, false, false>", "k2_residue_gemm<2, 1, 2, false>", "k3_inverse_crt<4, 4, false, true>"),
             4: ("k1_input_transform<4, true, false>", "k2_residue_gemm<4, 1, 2, true>", "k3_inverse_crt<2, 4, true, false>")}
     for idx, kernels in want.items():

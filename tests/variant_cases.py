@@ -47,6 +47,11 @@ def _candidates():
     for C, hw, wide in itertools.product((60, 128, 192, 256), (8, 24, 40), (False, True)):
         add(1, C, 24, hw, hw, 3, 6, 1, (PRIMES16[:2] if wide else PRIMES8[:4]))
         add(1, C, 24, 30, 30, 3, 6, 1, (PRIMES16[:2] if wide else PRIMES8[:4]))      # 25 tiles: two tile blocks
+    # (b2) the same with fewer than 128 rows (the register-direct GEMM keeps those) and with 128 and more (LDS-tiled GEMM
+    #      from three tile blocks on), ragged row and tile blocks included
+    for C, K, hw in itertools.product((60, 128, 256), (24, 130, 200), (40, 64)):
+        add(1, C, K, hw, hw, 3, 6, 1, PRIMES8[:4])
+    add(1, 40, 136, 36, 36, 3, 7, 1, PRIMES8[:3])            # t = 9: a last point group with one point, LDS-tiled
     # (c) 64-row GEMM blocks: K >= 256, two or more channel blocks (even and odd), enough work items
     for C in (128, 192):
         add(3, C, 256, 64, 64, 3, 8, 1, PRIMES8[:4])
