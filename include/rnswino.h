@@ -173,6 +173,24 @@ int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const
 int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, int32_t H, int32_t W,
                          int32_t shift, int32_t pool, void *stream);
 
+/*
+ * Direct int8 convolution as an implicit GEMM on the matrix cores: the baseline the paper measures against (section 8,
+ * Tables 4 and 5: Im2col + INT8 GEMM), provided so that the two paths can be timed on the same chip.  Same result as
+ * rnswino_conv2d (the exact int32 convolution, correlation orientation of section 3.1, stride 1), no RNS, no transforms.
+ *   rnswino_direct_filter_pack: w_dev int8 [K][C][r][r] -> wt_dev, rnswino_direct_filter_bytes(C, K, r) bytes, 16-byte
+ *     aligned, in matrix-core fragment order (ahead of time: the weights are constants of the layer);
+ *   rnswino_direct_conv2d: x_dev int8 [N][C][H][W], y_dev int32 [N][K][Ho][Wo]; workspace_dev holds
+ *     rnswino_direct_workspace_bytes(N, C, H, W, pad) bytes (16-byte aligned): the activations copied once into a
+ *     channel-innermost, zero-bordered layout.  No im2col matrix is written: operand fragments are gathered from that copy.
+ * Nothing is allocated or synchronised; kernels are enqueued on `stream`.  r <= 16; sizes whose 32-bit offsets would
+ * overflow are RNSWINO_E_UNSUPPORTED (the byte counts are then 0).
+ */
+size_t rnswino_direct_filter_bytes(int32_t C, int32_t K, int32_t r);
+size_t rnswino_direct_workspace_bytes(int32_t N, int32_t C, int32_t H, int32_t W, int32_t pad);
+int rnswino_direct_filter_pack(const int8_t *w_dev, void *wt_dev, int32_t C, int32_t K, int32_t r, void *stream);
+int rnswino_direct_conv2d(const int8_t *x_dev, const void *wt_dev, int32_t *y_dev, int32_t N, int32_t C, int32_t K, int32_t H,
+                          int32_t W, int32_t r, int32_t pad, void *workspace_dev, void *stream);
+
 /* ---- query / test surface ---- */
 
 /* Copy one transform matrix (which = RNSWINO_MATRIX_*, modulus_idx < n_moduli) to host_out (row-major int32). */

@@ -17,6 +17,7 @@ EXPORTED_SYMBOLS = (
     "rnswino_plan", "rnswino_plan_destroy", "rnswino_output_dims", "rnswino_filter_bytes",
     "rnswino_workspace_bytes", "rnswino_filter_transform", "rnswino_conv2d", "rnswino_conv2d_requant",
     "rnswino_conv2d_events", "rnswino_conv2d_static",
+    "rnswino_direct_filter_bytes", "rnswino_direct_workspace_bytes", "rnswino_direct_filter_pack", "rnswino_direct_conv2d",
     "rnswino_requant_pool",
     "rnswino_plan_get_matrix", "rnswino_plan_get_table", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
     "rnswino_plan_describe", "rnswino_kernel_variants",
@@ -73,6 +74,14 @@ def lib():
         L.rnswino_conv2d_events.restype = ctypes.c_int
         L.rnswino_conv2d_static.argtypes = [vp, vp, vp, vp, vp]
         L.rnswino_conv2d_static.restype = ctypes.c_int
+        L.rnswino_direct_filter_bytes.argtypes = [i32, i32, i32]
+        L.rnswino_direct_filter_bytes.restype = ctypes.c_size_t
+        L.rnswino_direct_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.rnswino_direct_workspace_bytes.restype = ctypes.c_size_t
+        L.rnswino_direct_filter_pack.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.rnswino_direct_filter_pack.restype = ctypes.c_int
+        L.rnswino_direct_conv2d.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+        L.rnswino_direct_conv2d.restype = ctypes.c_int
         L.rnswino_requant_pool.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp]
         L.rnswino_requant_pool.restype = ctypes.c_int
         L.rnswino_plan_get_matrix.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
@@ -191,6 +200,23 @@ STATIC_WORKSPACE_BYTES = 16 << 20
 
 def rnswino_conv2d_static(plan: Plan, x_dev, U_dev, y_dev, stream: int = 0) -> None:
     _check(lib().rnswino_conv2d_static(plan.handle, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev), stream), "rnswino_conv2d_static")
+
+
+def rnswino_direct_filter_bytes(C: int, K: int, r: int) -> int:
+    return int(lib().rnswino_direct_filter_bytes(C, K, r))
+
+
+def rnswino_direct_workspace_bytes(N: int, C: int, H: int, W: int, pad: int) -> int:
+    return int(lib().rnswino_direct_workspace_bytes(N, C, H, W, pad))
+
+
+def rnswino_direct_filter_pack(w_dev, wt_dev, C: int, K: int, r: int, stream: int = 0) -> None:
+    _check(lib().rnswino_direct_filter_pack(_ptr(w_dev), _ptr(wt_dev), C, K, r, stream), "rnswino_direct_filter_pack")
+
+
+def rnswino_direct_conv2d(x_dev, wt_dev, y_dev, N, C, K, H, W, r, pad, workspace_dev, stream: int = 0) -> None:
+    _check(lib().rnswino_direct_conv2d(_ptr(x_dev), _ptr(wt_dev), _ptr(y_dev), N, C, K, H, W, r, pad, _ptr(workspace_dev), stream),
+           "rnswino_direct_conv2d")
 
 
 def rnswino_requant_pool(y_dev, a_dev, planes: int, H: int, W: int, shift: int, pool: bool, stream: int = 0) -> None:

@@ -16,6 +16,7 @@
 #include <string>
 #include <vector>
 
+#include "k_direct_conv.hpp"
 #include "k_filter_transform.hpp"
 #include "k_glue.hpp"
 #include "k_input_transform.hpp"
@@ -559,6 +560,71 @@ int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, c
   len += std::snprintf(buf + len, sizeof(buf) - len, "conversion=%s\n", conv);
   if (host_out && capacity > (size_t)len) std::memcpy(host_out, buf, (size_t)len + 1);
   return (int64_t)len + 1;
+}
+
+// ---- direct convolution (the comparison baseline of section 8) ----
+static int direct_params(int32_t N, int32_t C, int32_t K, int32_t H, int32_t W, int32_t r, int32_t pad, DirectParams &P) {
+  if (N <= 0 || C <= 0 || K <= 0 || H <= 0 || W <= 0 || r <= 0 || pad < 0) return RNSWINO_E_INVALID;
+  const long long Ho = (long long)H + 2LL * pad - r + 1, Wo = (long long)W + 2LL * pad - r + 1;
+  if (Ho <= 0 || Wo <= 0) return RNSWINO_E_INVALID;
+  if (r > 16) return RNSWINO_E_UNSUPPORTED;
+  if ((unsigned __int128)16384u * (unsigned)r * (unsigned)r * (unsigned)C > 2147483647u) return RNSWINO_E_UNSUPPORTED;   // int32 sums
+  P.N = N; P.C = C; P.K = K; P.H = H; P.W = W; P.r = r; P.pad = pad;
+  P.Ho = (int)Ho; P.Wo = (int)Wo; P.Hp = H + 2 * pad; P.Wp = W + 2 * pad;
+  P.Cp = (C + 63) / 64 * 64; P.Kp = (K + 15) / 16 * 16;
+  const long long npix = (long long)N * Ho * Wo, xt = (long long)N * P.Hp * P.Wp * P.Cp;
+  if (npix >= (1LL << 28) || xt >= (1LL << 31) || (long long)r * r * P.Kp * P.Cp >= (1LL << 31)) return RNSWINO_E_UNSUPPORTED;   // 32-bit offsets
+  P.npix = (int)npix;
+  return RNSWINO_OK;
+}
+
+size_t rnswino_direct_filter_bytes(int32_t C, int32_t K, int32_t r) {
+  DirectParams P;
+  if (direct_params(1, C, K, r, r, r, 0, P) != RNSWINO_OK) return 0;
+  return align256((size_t)r * r * P.Kp * P.Cp);
+}
+
+size_t rnswino_direct_workspace_bytes(int32_t N, int32_t C, int32_t H, int32_t W, int32_t pad) {
+  DirectParams P;
+  if (direct_params(N, C, 1, H, W, 1, pad, P) != RNSWINO_OK) return 0;
+  return align256((size_t)N * P.Hp * P.Wp * P.Cp);
+}
+
+int rnswino_direct_filter_pack(const int8_t *w_dev, void *wt_dev, int32_t C, int32_t K, int32_t r, void *stream) {
+  if (!w_dev || !wt_dev) return RNSWINO_E_INVALID;
+  if ((uintptr_t)wt_dev & 15) return RNSWINO_E_INVALID;
+  DirectParams P;
+  const int rc = direct_params(1, C, K, r, r, r, 0, P);
+  if (rc != RNSWINO_OK) return rc;
+  const long long total = (long long)r * r * P.Kp * (P.Cp / 16);
+  hipLaunchKernelGGL(k_direct_pack_filter, dim3(blocks_for(total, 256)), dim3(256), 0, (hipStream_t)stream, P, w_dev, (int8_t *)wt_dev);
+  return launch_status();
+}
+
+int rnswino_direct_conv2d(const int8_t *x_dev, const void *wt_dev, int32_t *y_dev, int32_t N, int32_t C, int32_t K, int32_t H,
+                          int32_t W, int32_t r, int32_t pad, void *workspace_dev, void *stream) {
+  if (!x_dev || !wt_dev || !y_dev || !workspace_dev) return RNSWINO_E_INVALID;
+  if (((uintptr_t)wt_dev | (uintptr_t)workspace_dev) & 15) return RNSWINO_E_INVALID;
+  DirectParams P;
+  const int rc = direct_params(N, C, K, H, W, r, pad, P);
+  if (rc != RNSWINO_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  int8_t *xt = (int8_t *)workspace_dev;
+  const long long tblocks = (long long)N * P.Hp * (P.Cp / 64) * ((P.Wp + 63) / 64);
+  hipLaunchKernelGGL(k_direct_to_nhwc, dim3((unsigned)tblocks), dim3(256), 0, st, P, x_dev, xt);
+  // block shape: 128 x 128 when that still gives the chip two workgroups per compute unit, else 128 x 64, else 64 x 64;
+  // layers with at most 64 filters take 64 x 256
+  const long long nkb = P.Kp / 16, ntb = (P.npix + 15) / 16;
+  auto blocks = [&](int brf, int btf) { return ((nkb + brf - 1) / brf) * (((ntb + btf - 1) / btf + 7) / 8 * 8); };
+  if (P.Kp <= 64 && blocks(4, 16) >= 512)
+    hipLaunchKernelGGL((k_direct_conv<1, 4, 4, 4, 3>), dim3((unsigned)blocks(4, 16)), dim3(256), 0, st, P, xt, (const int8_t *)wt_dev, y_dev);
+  else if (P.Kp > 64 && blocks(8, 8) >= 512)
+    hipLaunchKernelGGL((k_direct_conv<2, 2, 4, 4, 3>), dim3((unsigned)blocks(8, 8)), dim3(256), 0, st, P, xt, (const int8_t *)wt_dev, y_dev);
+  else if (P.Kp > 64 && blocks(8, 4) >= 512)
+    hipLaunchKernelGGL((k_direct_conv<4, 1, 2, 4, 4>), dim3((unsigned)blocks(8, 4)), dim3(256), 0, st, P, xt, (const int8_t *)wt_dev, y_dev);
+  else
+    hipLaunchKernelGGL((k_direct_conv<4, 1, 1, 4, 4>), dim3((unsigned)blocks(4, 4)), dim3(256), 0, st, P, xt, (const int8_t *)wt_dev, y_dev);
+  return launch_status();
 }
 
 int rnswino_requant_pool(const int32_t *y_dev, int8_t *a_dev, int64_t planes, int32_t H, int32_t W, int32_t shift,
