@@ -40,12 +40,94 @@ def fused_glue_supported(m: int, Ho: int, Wo: int, pool: bool) -> bool:
     return (not pool) or (m in (4, 8) and Ho % 2 == 0 and Wo % 4 == 0)
 
 
+MARGIN = 0.03            # a candidate replaces the specified setting only if it is faster by more than this fraction
+WIDE_PAIR = (65521, 65519)
+
+
+def _time_layer(N, C, K, H, W, r, m, pad, moduli, flags, glue, dev, x, w, iters, warmup, rotate_bytes=300 << 20):
+    """Microseconds per call of one layer as a chain runs it, the transformed filter taken from a rotation of copies larger
+    than the on-chip caches (in a network every layer's filter comes from HBM)."""
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, flags, device=dev)
+    layer.set_weights(w)
+    p = layer.plan
+    copies = [layer.U] + [layer.U.clone() for _ in range(max(1, min(15, rotate_bytes // max(1, layer.U.numel()))))]
+    st = torch.cuda.current_stream(dev).cuda_stream
+    if glue is None:
+        step = lambda k: B.rnswino_conv2d(p, x, copies[k % len(copies)], layer.y, layer.workspace, st)
+    else:
+        shift, pool = glue
+        act = torch.empty((N, K, p.Ho // 2, p.Wo // 2) if pool else (N, K, p.Ho, p.Wo), dtype=torch.int8, device=dev)
+        if fused_glue_supported(m, p.Ho, p.Wo, bool(pool)):
+            step = lambda k: B.rnswino_conv2d_requant(p, x, copies[k % len(copies)], act, shift, pool, layer.workspace, st)
+        else:
+            def step(k):
+                B.rnswino_conv2d(p, x, copies[k % len(copies)], layer.y, layer.workspace, st)
+                B.rnswino_requant_pool(layer.y, act, N * K, p.Ho, p.Wo, shift, pool, st)
+    for k in range(warmup):
+        step(k)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize(dev)
+    start.record()
+    for k in range(iters):
+        step(warmup + k)
+    stop.record()
+    torch.cuda.synchronize(dev)
+    return start.elapsed_time(stop) * 1e3 / iters
+
+
+def number_system_candidates(C: int, r: int, moduli, flags: int = 0):
+    """The layer's own moduli set first, then the alternatives whose dynamic range holds its worst case 2^14 r^2 C
+    (sections 3 and 8; a range the caller trusts for his own set says nothing about another one): the two 16-bit moduli,
+    and three 8-bit moduli where four were specified but three suffice."""
+    worst = (1 << 14) * r * r * C
+    out = [tuple(moduli)]
+    for cand in (WIDE_PAIR, (251, 241, 239)):
+        prod = 1
+        for p in cand:
+            prod *= p
+        if cand not in out and worst <= (prod - 1) // 2 and (len(cand) < len(moduli) or cand == WIDE_PAIR):
+            out.append(cand)
+    return out
+
+
+def table2_reduction(m: int, r: int, moduli) -> float:
+    """The paper's predictor for this choice (section 7, Table 2): multiplications of the direct convolution per
+    multiplication of the RNS-Winograd GEMM, a 16-bit multiplication counted as one."""
+    return multiplication_reduction(m, r, len(moduli))
+
+
+def select_number_system(N, C, K, H, W, r, m, pad, moduli, iters: int = 10, warmup: int = 3, device="cuda:0", glue=None,
+                         flags: int = 0):
+    """Times the layer with every candidate moduli set (number_system_candidates) and returns (chosen, {set: microseconds}).
+    The specified set stays unless a candidate beats it by more than MARGIN (run-to-run noise must not pick).  Whatever is
+    chosen computes the same exact result."""
+    if not torch.cuda.is_available():
+        raise RuntimeError("rnswino needs a GPU: there is no CPU execution path")
+    dev = torch.device(device)
+    gen = torch.Generator(device="cpu").manual_seed(12216)
+    x = torch.randint(-128, 128, (N, C, H, W), dtype=torch.int8, generator=gen).to(dev)
+    w = torch.randint(-128, 128, (K, C, r, r), dtype=torch.int8, generator=gen)
+    times = {}
+    for cand in number_system_candidates(C, r, moduli, flags):
+        try:
+            times[cand] = _time_layer(N, C, K, H, W, r, m, pad, cand, flags, glue, dev, x, w, iters, warmup)
+        except B.RnsWinoError:
+            continue
+    base = tuple(moduli)
+    best = min(times, key=times.get)
+    if best != base and base in times and times[best] > (1.0 - MARGIN) * times[base]:
+        best = base
+    return best, times
+
+
 def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: int = 20, warmup: int = 3,
-                       device="cuda:0", glue=None, flags: int = 0):
+                       device="cuda:0", glue=None, flags: int = 0, prefer=None):
     """Times the layer for every candidate m on synthetic int8 data of the layer's shape.
 
     Without `glue` a timed step is one rnswino_conv2d call (int32 output).  With glue = (shift, pool) it is the layer as
     a chain runs it: rnswino_conv2d_requant where the library supports it, else rnswino_conv2d + rnswino_requant_pool.
+    The transformed filter rotates over copies larger than the caches, as in a network.  `prefer`: the specified tile; it is
+    kept unless another one is faster by more than MARGIN.
     Returns (best_m, {m: microseconds per call}).  Candidates the plan refuses (range, size limits) are left out.
     """
     if not torch.cuda.is_available():
@@ -59,34 +141,12 @@ def select_output_tile(N, C, K, H, W, r, pad, moduli, candidates=None, iters: in
     times = {}
     for m in candidates:
         try:
-            layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, flags, device=dev)
+            times[m] = _time_layer(N, C, K, H, W, r, m, pad, moduli, flags, glue, dev, x, w, iters, warmup)
         except B.RnsWinoError:
             continue
-        layer.set_weights(w)
-        step = lambda: layer.forward(x)
-        if glue is not None:
-            shift, pool = glue
-            p = layer.plan
-            act = torch.empty((N, K, p.Ho // 2, p.Wo // 2) if pool else (N, K, p.Ho, p.Wo), dtype=torch.int8, device=dev)
-            st = torch.cuda.current_stream(dev).cuda_stream
-            if fused_glue_supported(m, p.Ho, p.Wo, bool(pool)):
-                step = lambda: B.rnswino_conv2d_requant(p, x, layer.U, act, shift, pool, layer.workspace, st)
-            else:
-                def step():
-                    B.rnswino_conv2d(p, x, layer.U, layer.y, layer.workspace, st)
-                    B.rnswino_requant_pool(layer.y, act, N * K, p.Ho, p.Wo, shift, pool, st)
-        for _ in range(warmup):
-            step()
-        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize(dev)
-        start.record()
-        for _ in range(iters):
-            step()
-        stop.record()
-        torch.cuda.synchronize(dev)
-        times[m] = start.elapsed_time(stop) * 1e3 / iters
-        del layer
     if not times:
         raise ValueError("no output tile is accepted for this layer")
     best = min(times, key=times.get)
+    if prefer is not None and prefer in times and best != prefer and times[best] > (1.0 - MARGIN) * times[prefer]:
+        best = prefer           # within the margin of the specified tile: keep it
     return best, times

@@ -17,7 +17,7 @@ def test_algorithmic_bytes_of_workload_2():
     cfg = si.layer_config(2)
     b = bench.stage_bytes(cfg, _plan_like(cfg))
     x, v, u, y = 802816, 5017600, 26214400, 3211264
-    assert b == {"input_transform": x + v, "residue_gemm": u + 2 * v, "inverse_transform_mrc": v + y}
+    assert b == {"input_transform": x + v, "residue_gemm": u + 2 * v, "inverse_transform_crt": v + y}
 
 
 def test_algorithmic_bytes_of_the_16_bit_workload():
@@ -34,4 +34,4 @@ def test_matrix_core_operation_counts_of_workload_2():
     ops = bench.stage_mfma_ops(cfg, _plan_like(cfg))
     assert ops["residue_gemm"] == 2.0 * 400 * 256 * 256 * 64
     assert ops["input_transform"] == 2.0 * 4 * 112 * 128 * 49 * 256
-    assert ops["inverse_transform_mrc"] == 2.0 * 4 * 64 * 128 * 256 * 49
+    assert ops["inverse_transform_crt"] == 2.0 * 4 * 64 * 128 * 256 * 49

@@ -246,6 +246,54 @@ def test_vgg16_stack_with_measured_tiles():
         assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
 
 
+def test_vgg16_stack_with_mixed_number_systems():
+    """Layers of one chain in different number systems: every second layer over the two 16-bit moduli (with the fused
+    re-quantisation and pooling of that path), the others over their 8-bit sets; every layer's activations are the CPU chain's."""
+    from paper_2007_12216_amd.stack import ConvStack
+    print("stack mixed number systems", flush=True)
+    batch, hw = 2, 32
+    layers = si.vgg16_stack(batch=batch, hw=hw)
+    for li, l in enumerate(layers):
+        if li % 2 == 1:
+            l["moduli"] = (65521, 65519)
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
+    stack = ConvStack(layers)
+    stack.set_weights(weights)
+    stack.forward(torch.from_numpy(x).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref_acts, _ = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+
+
+def test_number_system_selection_times_the_candidates_and_the_stack_stays_exact():
+    """Per-layer choice between the 8-bit moduli set of the range bound and the two 16-bit moduli (end of the paper's
+    section 7), by timing both; the specified set stays unless the other is faster by more than the margin."""
+    from paper_2007_12216_amd import select
+    from paper_2007_12216_amd.stack import ConvStack
+    print("number system selection", flush=True)
+    four = (251, 241, 239, 233)
+    assert select.number_system_candidates(256, 3, four) == [four, (65521, 65519)]
+    assert select.number_system_candidates(3, 3, four) == [four, (65521, 65519), (251, 241, 239)]
+    assert select.number_system_candidates(20000, 3, four, flags=rn.FLAG_ALLOW_UNCHECKED_RANGE) == [four]   # beyond both ranges
+    best, times = select.select_number_system(1, 64, 64, 28, 28, 3, 8, 1, four, iters=5)
+    assert set(times) == {four, (65521, 65519)} and best in times
+    assert best == four or times[best] <= (1.0 - select.MARGIN) * times[four]
+    batch, hw = 2, 32
+    layers = si.vgg16_stack(batch=batch, hw=hw)
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
+    stack = ConvStack(layers, number_systems=True)
+    print("moduli", [l["moduli"] for l in stack.cfg], flush=True)
+    stack.set_weights(weights)
+    stack.forward(torch.from_numpy(x).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref_acts, _ = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+
+
 def test_vgg16_stack_in_the_papers_setting():
     """Three 8-bit moduli on every layer with the range trusted (section 8 of the paper) instead of four from the worst-case
     bound: the outputs of the seeded data stay inside the dynamic range, so the chain is still the oracle's."""
