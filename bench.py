@@ -199,8 +199,23 @@ def bench_layer(idx, steps, warmup, dev, with_cpu, warm=False, events=True):
                 stage_ms[nm] += evs.elapsed_ms(ev[k][2 * j], ev[k][2 * j + 1])
         for nm in names:
             stage_ms[nm] /= steps
-        evs.destroy_all()
         last_set = (warmup + steps - 1) % n_sets
+        # the floor of each stage: a kernel that does nothing, launched with that stage's grid
+        grids = {}
+        for nm, g in zip(names, rn.rnswino_plan_describe(plan, 0)["grids"]):
+            gx, _, gy = g.split()[0].split("=")[1].partition("x")
+            grids[nm] = (int(gx), int(gy or 1))
+        floor_ms = {nm: 0.0 for nm in names}
+        reps = min(steps, 50)
+        fe = [[(evs.create(), evs.create()) for _ in names] for _ in range(reps)]
+        for k in range(reps):
+            for j, nm in enumerate(names):
+                rn.rnswino_debug_empty_launch(grids[nm][0], grids[nm][1], stream, fe[k][j][0], fe[k][j][1])
+        sync()
+        for k in range(reps):
+            for j, nm in enumerate(names):
+                floor_ms[nm] += evs.elapsed_ms(fe[k][j][0], fe[k][j][1]) / reps
+        evs.destroy_all()
 
     described = rn.rnswino_plan_describe(plan, 0)
     kernel_of = dict(zip(names, described["kernels"]))
@@ -222,6 +237,8 @@ def bench_layer(idx, steps, warmup, dev, with_cpu, warm=False, events=True):
                     # matrix-core utilisation per stage: int8 MFMA operations issued / duration / 5 POP/s dense int8 peak
                     "stage_mfma_frac": {nm: round(mfma_ops[nm] / (stage_ms[nm] * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4)
                                         for nm in names},
+                    # duration of a kernel that does nothing on the same grid (dispatch, ramp-up, completion)
+                    "stage_empty_grid_us": {nm: round(floor_ms[nm] * 1e3, 2) for nm in names},
                     "kernels": kernel_of, "conversion": described["conversion"]}
 
     sync()

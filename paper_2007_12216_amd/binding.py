@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = (
     "rnswino_direct_filter_bytes", "rnswino_direct_workspace_bytes", "rnswino_direct_filter_pack", "rnswino_direct_conv2d",
     "rnswino_requant_pool",
     "rnswino_plan_get_matrix", "rnswino_plan_get_table", "rnswino_plan_get_mrc_inverse", "rnswino_plan_dynamic_range",
-    "rnswino_plan_describe", "rnswino_kernel_variants",
+    "rnswino_plan_describe", "rnswino_kernel_variants", "rnswino_debug_empty_launch",
     "rnswino_debug_stage", "rnswino_strerror",
 )
 
@@ -92,6 +92,8 @@ def lib():
         L.rnswino_plan_get_mrc_inverse.restype = ctypes.c_int
         L.rnswino_plan_describe.argtypes = [vp, i32, ctypes.c_char_p, ctypes.c_size_t]
         L.rnswino_plan_describe.restype = i64
+        L.rnswino_debug_empty_launch.argtypes = [u32, u32, vp, vp, vp]
+        L.rnswino_debug_empty_launch.restype = ctypes.c_int
         L.rnswino_kernel_variants.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
         L.rnswino_kernel_variants.restype = i64
         L.rnswino_plan_dynamic_range.argtypes = [vp]
@@ -267,6 +269,11 @@ def rnswino_plan_describe(plan: Plan, output_mode: int = 0) -> dict:
             kernels.append(name + ">")
             grids.append(rest)
     return {"kernels": kernels, "grids": grids, "conversion": conversion, "text": text}
+
+
+def rnswino_debug_empty_launch(grid_x: int, grid_y: int, stream: int = 0, start_event: int = 0, stop_event: int = 0) -> None:
+    _check(lib().rnswino_debug_empty_launch(grid_x, grid_y, stream, start_event or None, stop_event or None),
+           "rnswino_debug_empty_launch")
 
 
 def rnswino_kernel_variants() -> list:

@@ -27,4 +27,8 @@ __global__ void k_requant_pool(const int32_t *__restrict__ y, int8_t *__restrict
   }
 }
 
+// A kernel that does nothing: timing it with a stage's grid gives the part of that stage's duration that is dispatch,
+// ramp-up and completion rather than work (rnswino_debug_empty_launch).
+__global__ __launch_bounds__(256) void k_empty(int unused) { (void)unused; }
+
 }  // namespace rnswino

@@ -516,6 +516,15 @@ int rnswino_conv2d_events(const rnswino_plan_t *plan, const int8_t *x_dev, const
   return conv2d_impl(plan, x_dev, U_dev, y_dev, workspace_dev, stream, events);
 }
 
+int rnswino_debug_empty_launch(uint32_t grid_x, uint32_t grid_y, void *stream, void *start_event, void *stop_event) {
+  if (grid_x == 0 || grid_y == 0 || grid_y > 65535u) return RNSWINO_E_INVALID;
+  Timing tm;
+  tm.start = (hipEvent_t)start_event;
+  tm.stop = (hipEvent_t)stop_event;
+  launch(k_empty, dim3(grid_x, grid_y), 0, (hipStream_t)stream, tm, 0);
+  return launch_status();
+}
+
 int64_t rnswino_kernel_variants(char *host_out, size_t capacity) {
   const std::string all = all_kernel_variants();
   if (host_out && capacity > all.size()) std::memcpy(host_out, all.c_str(), all.size() + 1);

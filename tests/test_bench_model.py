@@ -35,3 +35,26 @@ def test_matrix_core_operation_counts_of_workload_2():
     assert ops["residue_gemm"] == 2.0 * 400 * 256 * 256 * 64
     assert ops["input_transform"] == 2.0 * 4 * 112 * 128 * 49 * 256
     assert ops["inverse_transform_crt"] == 2.0 * 4 * 64 * 128 * 256 * 49
+
+
+def test_recorded_traffic_belongs_to_the_kernels_workload_2_launches():
+    """profiles/hbm_traffic.json holds counter-derived HBM bytes per kernel instantiation; bench.py reports them as
+    roofline.traffic only for an instantiation of that name.  A change of the dispatch must not leave stale figures behind:
+    the recorded workload-2 kernels are exactly the ones the plan launches now, and their algorithmic bytes are bench.py's."""
+    import json
+    import os
+    import paper_2007_12216_amd as rn
+    table = json.load(open(os.path.join(os.path.dirname(os.path.abspath(bench.__file__)), "profiles", "hbm_traffic.json")))
+    recorded = {e["kernel"]: e for e in table["kernels"] if e["workload"] == "config2"}
+    cfg = si.layer_config(2)
+    plan = rn.rnswino_plan(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["r"], cfg["m"], cfg["pad"], cfg["moduli"],
+                           flags=rn.FLAG_HOST_ONLY)
+    launched = rn.rnswino_plan_describe(plan, 0)["kernels"]
+    assert sorted(recorded) == sorted(launched)
+    want = bench.stage_bytes(cfg, _plan_like(cfg))
+    for stage, kernel in zip(bench.STAGES, launched):
+        e = recorded[kernel]
+        assert e["algorithmic_bytes"] == want[stage]
+        assert e["hbm_bytes"] == e["hbm_read_bytes"] + e["hbm_write_bytes"] and 0.9 * want[stage] < e["hbm_bytes"] < 2.0 * want[stage]
+        assert bench.recorded_traffic(kernel)["hbm_bytes"] == e["hbm_bytes"] and e["commit"]
+    assert bench.recorded_traffic("k2_residue_gemm<9, 9, 9, false>") is None
