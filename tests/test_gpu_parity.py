@@ -449,6 +449,37 @@ def test_random_shapes_are_bit_exact(case):
     assert np.array_equal(y, direct_conv2d(x, w, pad))
 
 
+def _random_cases_many_rows(count, seed):
+    """Seeded random layers with 128 and more filters and more than 32 tiles: the shapes the LDS-tiled GEMM takes (ragged row
+    and tile blocks, one to five 64-channel steps, point groups with one to four points)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        r = int(rng.choice([1, 3, 3, 5]))
+        m = int(rng.integers(3, 9))
+        N = int(rng.integers(1, 4))
+        C = int(rng.choice([7, 40, 64, 100, 130, 260, 300]))
+        K = int(rng.choice([128, 136, 200, 260]))
+        H, W = int(rng.integers(28, 72)), int(rng.integers(28, 72))
+        pad = int(rng.integers(0, r))
+        moduli = (251, 241, 239, 233) if (1 << 14) * r * r * C > 7228674 else (251, 241, 239)
+        if (1 << 14) * r * r * C > (251 * 241 * 239 * 233 - 1) // 2:
+            continue
+        cases.append((N, C, K, H, W, r, m, pad, moduli))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases_many_rows(14, 77))
+def test_random_shapes_with_many_rows_are_bit_exact(case):
+    N, C, K, H, W, r, m, pad, moduli = case
+    print("random case (many rows)", case, flush=True)
+    x = si.int8_tensor(503, (N, C, H, W))
+    w = si.int8_tensor(504, (K, C, r, r))
+    layer, y = run_layer(N, C, K, H, W, r, m, pad, moduli, x, w)
+    print(rn.rnswino_plan_describe(layer.plan)["kernels"], flush=True)
+    assert np.array_equal(y, direct_conv2d(x, w, pad))
+
+
 def test_two_streams_with_their_own_workspaces():
     """One plan and one transformed filter, two calls in flight on two streams, each with its own workspace and output:
     the entry point keeps no state between calls, so both results are the oracle's."""
