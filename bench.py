@@ -200,21 +200,38 @@ def bench_layer(idx, steps, warmup, dev, with_cpu, warm=False, events=True):
         for nm in names:
             stage_ms[nm] /= steps
         last_set = (warmup + steps - 1) % n_sets
-        # the floor of each stage: a kernel that does nothing, launched with that stage's grid
+        # the floor of each stage: a chain of kernels that do nothing on that stage's grid, replayed from a HIP graph (so that
+        # the host's launch rate does not enter), time per launch
         grids = {}
         for nm, g in zip(names, rn.rnswino_plan_describe(plan, 0)["grids"]):
             gx, _, gy = g.split()[0].split("=")[1].partition("x")
             grids[nm] = (int(gx), int(gy or 1))
-        floor_ms = {nm: 0.0 for nm in names}
-        reps = min(steps, 50)
-        fe = [[(evs.create(), evs.create()) for _ in names] for _ in range(reps)]
-        for k in range(reps):
-            for j, nm in enumerate(names):
-                rn.rnswino_debug_empty_launch(grids[nm][0], grids[nm][1], stream, fe[k][j][0], fe[k][j][1])
-        sync()
-        for k in range(reps):
-            for j, nm in enumerate(names):
-                floor_ms[nm] += evs.elapsed_ms(fe[k][j][0], fe[k][j][1]) / reps
+        floor_ms = {}
+        for nm in names:
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream(dev))
+                with torch.cuda.stream(side):
+                    rn.rnswino_debug_empty_launch(grids[nm][0], grids[nm][1], side.cuda_stream)
+                torch.cuda.current_stream(dev).wait_stream(side)
+                sync()
+                graph, chain = torch.cuda.CUDAGraph(), 200
+                with torch.cuda.graph(graph):
+                    cs = torch.cuda.current_stream(dev).cuda_stream
+                    for _ in range(chain):
+                        rn.rnswino_debug_empty_launch(grids[nm][0], grids[nm][1], cs)
+                for _ in range(2):
+                    graph.replay()
+                sync()
+                t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0.record()
+                graph.replay()
+                t1.record()
+                sync()
+                floor_ms[nm] = t0.elapsed_time(t1) / chain
+                del graph
+            except Exception:        # graph capture unavailable: the floor is simply not reported
+                floor_ms[nm] = None
         evs.destroy_all()
 
     described = rn.rnswino_plan_describe(plan, 0)
@@ -237,8 +254,8 @@ def bench_layer(idx, steps, warmup, dev, with_cpu, warm=False, events=True):
                     # matrix-core utilisation per stage: int8 MFMA operations issued / duration / 5 POP/s dense int8 peak
                     "stage_mfma_frac": {nm: round(mfma_ops[nm] / (stage_ms[nm] * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4)
                                         for nm in names},
-                    # duration of a kernel that does nothing on the same grid (dispatch, ramp-up, completion)
-                    "stage_empty_grid_us": {nm: round(floor_ms[nm] * 1e3, 2) for nm in names},
+                    # time per launch of a dependent chain of kernels that do nothing on the same grid (dispatch, ramp-up, completion)
+                    "stage_empty_grid_us": {nm: (round(floor_ms[nm] * 1e3, 2) if floor_ms[nm] is not None else None) for nm in names},
                     "kernels": kernel_of, "conversion": described["conversion"]}
 
     sync()

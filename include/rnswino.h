@@ -229,8 +229,8 @@ int rnswino_plan_get_mrc_inverse(const rnswino_plan_t *plan, int l, int j, uint3
 int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, char *host_out, size_t capacity);
 
 /* Launches a kernel that does nothing on grid_x x grid_y workgroups of 256 threads, between two optional caller-created
- * hipEvent_t (passed as void*) that receive its start and stop timestamps: what a stage's duration would be with no work in
- * it (dispatch, ramp-up, completion).  For measurement (the time breakdown of section 8). */
+ * hipEvent_t (passed as void*, may be NULL) that receive its start and stop timestamps.  Chains of such launches measure what a
+ * stage's launch costs with no work in it (dispatch, ramp-up, completion).  For measurement (the time breakdown of section 8). */
 int rnswino_debug_empty_launch(uint32_t grid_x, uint32_t grid_y, void *stream, void *start_event, void *stop_event);
 
 /* Every kernel instantiation of the three hot stages the library can launch, one name per line in the form of
