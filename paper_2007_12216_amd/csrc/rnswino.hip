@@ -193,11 +193,12 @@ K2Choice choose_k2(const Dims &d) {
   c.NTB = ntb == 1 ? 1 : ntb == 2 ? 2 : 4;
   if (!c.wide && d.Kp >= 128) {
     // LDS-tiled kernel where it measured faster than the register-direct one (VGG16 stack at batch 8, the 256-channel
-    // layer at batch 1): 128 x 64 blocks for 33..64 tiles; 128 x 128 blocks for many tiles, unless the last tile block
-    // would be mostly padding (more than a tenth of the tile blocks wasted) on a contraction of several steps
+    // layer at batch 1): 128 x 64 blocks for 33..64 tiles; 128 x 128 blocks for many tiles and a contraction of two or
+    // more steps (with a single step the pipeline over the four points never fills), unless the last tile block would be
+    // mostly padding (more than a tenth of the tile blocks wasted)
     const int tb128 = (ntb + 7) / 8;
     const bool few = ntb == 3 || ntb == 4;
-    const bool many = ntb >= 5 && (ncb == 1 || tb128 * 80 <= ntb * 11);
+    const bool many = ntb >= 5 && ncb >= 2 && tb128 * 80 <= ntb * 11;
     if (few || many) {
       c.lds = true; c.KS = 0; c.NTB = 4;
       if (few) { c.WM = 4; c.WN = 1; c.RM = 2; c.S = 4; }
