@@ -302,7 +302,8 @@ def layer_name(cfg):
             f"F({cfg['m']}x{cfg['m']},{cfg['r']}x{cfg['r']}) moduli={list(cfg['moduli'])}")
 
 
-def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tiles=False, number_systems=False, per_layer=False):
+def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tiles=False, number_systems=False, per_layer=False,
+                weight_bound=False):
     """Workload 5: one step = one pass of the 13-layer VGG16 conv stack at batch 8 (conv, shift/clamp, pool chain)."""
     import numpy as np
     import torch
@@ -318,6 +319,13 @@ def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tile
         for l in layers:
             l["moduli"], l["flags"] = (251, 241, 239), rn.FLAG_ALLOW_UNCHECKED_RANGE
     weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    if weight_bound:
+        # moduli count per layer from the bound its own weights give, 128 * max_k sum |w[k]|, instead of the worst case
+        # 2^14 r^2 C: still a guarantee for every int8 input, but a statement about these weights
+        from paper_2007_12216_amd import select
+        for l, w in zip(layers, weights):
+            l["output_bound"] = select.output_bound_from_weights(w)
+            l["moduli"] = select.moduli_for_bound(l["output_bound"])
     x_np = si.int8_tensor(si.VGG16_SEED_X, (8, 3, 224, 224))
     stack = ConvStack(layers, measured_tiles=measured_tiles, number_systems=number_systems)
     stack.set_weights(weights)
@@ -409,6 +417,7 @@ def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tile
             ("output tile measured per layer" if measured_tiles else "F(8x8,3x3)") +
             (", number system measured per layer" if number_systems else "") +
             (", RNS(251,241,239) with a trusted range on every layer" if trusted_range else "") +
+            (", moduli count per layer from the bound of its own weights" if weight_bound else "") +
             ", shift/clamp + 2x2 max-pool fused into the inverse transform")
     return {"name": name, "ops": ops, "sec": sec, "rounds": rounds, "steps": steps, "warmup": warmup, "roofline": roofline,
             "bit_exact": bit_exact, "cpu": cpu, "tiles": [l["m"] for l in stack.cfg],
@@ -448,6 +457,9 @@ def main():
     ap.add_argument("--number-systems", action="store_true",
                     help="workload 5 only: pick every layer's number system (8-bit moduli from the range bound, or two 16-bit moduli) "
                          "by timing both")
+    ap.add_argument("--weight-bound", action="store_true",
+                    help="workload 5 only: moduli count per layer from the output bound its own weights give (128 max_k sum |w|) "
+                         "instead of the worst case 2^14 r^2 C")
     ap.add_argument("--per-layer", action="store_true", help="workload 5 only: add a per-layer, per-kernel table of durations")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -469,7 +481,8 @@ def main():
                                "rounds_ms_per_step": [round(v * 1e3, 5) for v in r["rounds"]]}
 
     if args.workload == 5:
-        r = bench_stack(K_steps, W_steps, dev, with_cpu, args.trusted_range, args.measured_tiles, args.number_systems, args.per_layer)
+        r = bench_stack(K_steps, W_steps, dev, with_cpu, args.trusted_range, args.measured_tiles, args.number_systems, args.per_layer,
+                        args.weight_bound)
         out = dict(common, value=round(r["ops"] / r["sec"] / 1e12, 3), steps=r["steps"], warmup=r["warmup"],
                    ms_per_step=round(r["sec"] * 1e3, 5),
                    config={"workload": r["name"], "output_tiles": r["tiles"], "moduli": r["moduli"],

@@ -50,8 +50,8 @@ enum {
   RNSWINO_E_NOT_COPRIME = -3,          /* two moduli share a factor (section 3: pairwise coprime)           */
   RNSWINO_E_POINT_NOT_INVERTIBLE = -4, /* a modulus shares a factor with a difference of two interpolation
                                           points, so a denominator of V^-1 has no inverse (section 5)       */
-  RNSWINO_E_RANGE = -5,                /* 2^14 r^2 C exceeds (prod m_i - 1)/2: the dynamic range of the RNS
-                                          cannot hold the worst-case output (sections 3, 5, 8)              */
+  RNSWINO_E_RANGE = -5,                /* 2^14 r^2 C (or the caller's output_bound) exceeds (prod m_i - 1)/2: the
+                                          dynamic range of the RNS cannot hold the output (sections 3, 5, 8) */
   RNSWINO_E_HIP = -6,                  /* a HIP runtime call or kernel launch failed                        */
   RNSWINO_E_NO_DEVICE = -7,            /* the plan was made host-only, or no GPU is present                 */
   RNSWINO_E_WORKSPACE = -8             /* rnswino_conv2d_static: the layer needs more workspace than
@@ -79,6 +79,12 @@ typedef struct {
   uint32_t moduli[8];       /* odd, pairwise coprime; either all in [3,253] (residues stored in 8 bits) or
                                all in [257,65521] (16 bits)                                                  */
   uint32_t flags;           /* RNSWINO_FLAG_*                                                                */
+  uint64_t output_bound;    /* 0: the range test uses the worst case 2^14 r^2 C of int8 operands.  Otherwise an upper
+                               bound on |y| that the caller guarantees for this layer, e.g. 128 * max_k sum_{c,i,j}
+                               |w[k][c][i][j]| for its actual weights (a proof, where the paper trusts a measured
+                               range, section 8): the range test and the choice of the conversion use it (if it is
+                               smaller than the worst case), so fewer moduli may pass.  With weights that exceed it
+                               the result is the true value reduced to the symmetric range of the moduli set.       */
 } rnswino_desc_t;
 
 /* Transform matrices modulo one modulus, entries in [-(p-1)/2, (p-1)/2] (section 5):

@@ -35,7 +35,7 @@ class _Desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int32), ("C", ctypes.c_int32), ("K", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("W", ctypes.c_int32), ("r", ctypes.c_int32), ("m", ctypes.c_int32), ("pad", ctypes.c_int32),
                 ("stride", ctypes.c_int32), ("n_moduli", ctypes.c_int32), ("moduli", ctypes.c_uint32 * 8),
-                ("flags", ctypes.c_uint32)]
+                ("flags", ctypes.c_uint32), ("output_bound", ctypes.c_uint64)]
 
 
 _lib = None
@@ -134,7 +134,7 @@ class Plan:
             _lib.rnswino_plan_destroy(h)
 
 
-def rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags: int = 0, stride: int = 1) -> Plan:
+def rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags: int = 0, stride: int = 1, output_bound: int = 0) -> Plan:
     d = _Desc()
     d.N, d.C, d.K, d.H, d.W, d.r, d.m, d.pad, d.stride = N, C, K, H, W, r, m, pad, stride
     d.n_moduli = len(moduli)
@@ -142,6 +142,7 @@ def rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags: int = 0, stride: int =
         for i, p in enumerate(moduli):
             d.moduli[i] = p
     d.flags = flags
+    d.output_bound = int(output_bound)
     out = ctypes.c_void_p()
     _check(lib().rnswino_plan(ctypes.byref(out), ctypes.byref(d)), "rnswino_plan")
     return Plan(out, d)

@@ -52,6 +52,13 @@ int resolve_scratch(int dev) {          // called with device `dev` current
   return RNSWINO_OK;
 }
 
+// The largest |y| the plan has to represent: the worst case 2^14 r^2 C of int8 operands (sections 3, 5, 8), or the
+// caller's tighter bound for the layer's actual weights (rnswino_desc_t::output_bound), whichever is smaller.
+unsigned __int128 output_bound(const rnswino_desc_t &desc, const Dims &d) {
+  const unsigned __int128 worst = (unsigned __int128)16384u * (unsigned)d.r * (unsigned)d.r * (unsigned)d.C;
+  return desc.output_bound != 0 && (unsigned __int128)desc.output_bound < worst ? (unsigned __int128)desc.output_bound : worst;
+}
+
 KParams make_params(const rnswino_plan_t *pl) {
   KParams P;
   std::memset(&P, 0, sizeof(P));
@@ -75,7 +82,7 @@ KParams make_params(const rnswino_plan_t *pl) {
     unsigned __int128 prod = 1;
     const unsigned __int128 cap = ((unsigned __int128)1 << 100);
     for (int i = 0; i < d.n; ++i) { prod *= pl->desc.moduli[i]; if (prod > cap) prod = cap; }
-    const unsigned __int128 worst = (unsigned __int128)16384u * (unsigned)d.r * (unsigned)d.r * (unsigned)d.C;
+    const unsigned __int128 worst = output_bound(pl->desc, d);
     P.quot32 = (worst * 20 <= prod * 9) ? 1 : 0;
     // Fast conversion: the binary32 sum of (a_i + 2^22) / p_i - B, B = 2^22 sum_i 1/p_i, stays within [-B, B]; it
     // takes n + 1 roundings of at most half an ulp of 2B each, and the rounded 1/p_i add at most 2B 2^-23 in all.
@@ -421,7 +428,7 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   for (int i = 0; i < d.n; ++i) { prod *= desc->moduli[i]; if (prod > cap) prod = cap; }
   const unsigned __int128 half = (prod - 1) / 2;
   pl->dyn_range = half > (unsigned __int128)INT64_MAX ? INT64_MAX : (int64_t)half;
-  const unsigned __int128 worst = (unsigned __int128)16384u * (unsigned)d.r * (unsigned)d.r * (unsigned)d.C;
+  const unsigned __int128 worst = output_bound(*desc, d);
   if (!(desc->flags & RNSWINO_FLAG_ALLOW_UNCHECKED_RANGE) && worst > half) { delete pl; return RNSWINO_E_RANGE; }
   std::memset(pl->mrc_inv, 0, sizeof(pl->mrc_inv));
   for (int l = 0; l < d.n; ++l)
@@ -741,7 +748,7 @@ const char *rnswino_strerror(int code) {
     case RNSWINO_E_UNSUPPORTED: return "unsupported configuration";
     case RNSWINO_E_NOT_COPRIME: return "moduli are not pairwise coprime";
     case RNSWINO_E_POINT_NOT_INVERTIBLE: return "a modulus shares a factor with an interpolation-point difference";
-    case RNSWINO_E_RANGE: return "dynamic range of the moduli set is below the worst-case output 2^14 r^2 C";
+    case RNSWINO_E_RANGE: return "dynamic range of the moduli set is below the output bound (worst case 2^14 r^2 C unless the caller gave a tighter one)";
     case RNSWINO_E_HIP: return "HIP runtime error";
     case RNSWINO_E_NO_DEVICE: return "plan is host-only or no GPU is available";
     case RNSWINO_E_WORKSPACE: return "the layer needs more workspace than the library's static buffer holds";

@@ -14,12 +14,12 @@ class ConvLayer:
     rnswino_conv2d on the current torch stream; nothing is computed in Python.
     """
 
-    def __init__(self, N, C, K, H, W, r, m, pad, moduli, flags: int = 0, device="cuda:0"):
+    def __init__(self, N, C, K, H, W, r, m, pad, moduli, flags: int = 0, device="cuda:0", output_bound: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("rnswino needs a GPU: there is no CPU execution path")
         self.device = torch.device(device)
         with torch.cuda.device(self.device):
-            self.plan = B.rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags)
+            self.plan = B.rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags, output_bound=output_bound)
         p = self.plan
         self.U = torch.empty(B.rnswino_filter_bytes(p), dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(B.rnswino_workspace_bytes(p), dtype=torch.uint8, device=self.device)

@@ -44,6 +44,26 @@ MARGIN = 0.03            # a candidate replaces the specified setting only if it
 WIDE_PAIR = (65521, 65519)
 
 
+def output_bound_from_weights(w) -> int:
+    """An upper bound on |y| of a layer with these int8 weights [K][C][r][r] and any int8 input: |x| <= 128, so
+    |y[k]| <= 128 * sum_{c,i,j} |w[k][c][i][j]|; the maximum over k.  For rnswino_desc_t::output_bound: with it the range test
+    of a plan is a statement about the layer's actual weights instead of the worst case 2^14 r^2 C (all |w| = 128)."""
+    import numpy as np
+    w = np.asarray(w)
+    return int(128 * np.abs(w.astype(np.int64)).reshape(w.shape[0], -1).sum(axis=1).max())
+
+
+def moduli_for_bound(bound: int, candidates=((251, 241, 239), (251, 241, 239, 233))):
+    """The first (smallest) candidate moduli set whose dynamic range (prod - 1) / 2 holds `bound` (sections 3 and 5)."""
+    for cand in candidates:
+        prod = 1
+        for p in cand:
+            prod *= p
+        if bound <= (prod - 1) // 2:
+            return tuple(cand)
+    raise ValueError("no candidate moduli set holds this bound")
+
+
 def _time_layer(N, C, K, H, W, r, m, pad, moduli, flags, glue, dev, x, w, iters, warmup, rotate_bytes=300 << 20):
     """Microseconds per call of one layer as a chain runs it, the transformed filter taken from a rotation of copies larger
     than the on-chip caches (in a network every layer's filter comes from HBM)."""

@@ -11,7 +11,8 @@ from .select import fused_glue_supported
 
 class ConvStack:
     def __init__(self, layers, device="cuda:0", measured_tiles: bool = False, number_systems: bool = False):
-        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool and optionally flags (plan flags)
+        """layers: list of dicts with N, C, K, H, W, r, m, pad, moduli, shift, pool and optionally flags (plan flags) and
+        output_bound (the caller's bound on |y| for the layer's weights, see select.output_bound_from_weights)
         (see synth_inputs.vgg16_stack).
 
         measured_tiles: replace every layer's output tile m by the fastest one for its shape, timed on the device with the
@@ -50,7 +51,7 @@ class ConvStack:
         with torch.cuda.device(self.device):
             for l in self.cfg:
                 p = B.rnswino_plan(l["N"], l["C"], l["K"], l["H"], l["W"], l["r"], l["m"], l["pad"], l["moduli"],
-                                   l.get("flags", 0))
+                                   l.get("flags", 0), output_bound=l.get("output_bound", 0))
                 self.plans.append(p)
                 self.U.append(torch.empty(B.rnswino_filter_bytes(p), dtype=torch.uint8, device=self.device))
                 ws_bytes = max(ws_bytes, B.rnswino_workspace_bytes(p))

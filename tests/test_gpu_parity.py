@@ -294,6 +294,56 @@ def test_number_system_selection_times_the_candidates_and_the_stack_stays_exact(
         assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
 
 
+def test_weight_derived_output_bound_is_tight_and_sufficient():
+    """Three moduli on a 64-channel layer, admitted by the bound 128 * max_k sum |w[k]| of its actual weights (the worst case
+    2^14 r^2 C would need four): exact on seeded inputs, and exact on the input that drives one filter's output to that bound
+    (x = -128 where the filter is positive, 127 where it is negative), which sits beyond 0.3 of the moduli product."""
+    from paper_2007_12216_amd import select
+    print("weight bound", flush=True)
+    N, C, K, H, W, r, m, pad, moduli = 1, 64, 32, 16, 16, 3, 8, 1, (251, 241, 239)
+    w = si.int8_tensor(9201, (K, C, r, r))
+    bound = select.output_bound_from_weights(w)
+    with pytest.raises(rn.RnsWinoError):
+        rn.rnswino_plan(N, C, K, H, W, r, m, pad, moduli, flags=rn.FLAG_HOST_ONLY)
+    from paper_2007_12216_amd.layer import ConvLayer
+    layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli, output_bound=bound)
+    layer.set_weights(w)
+    k0 = int(np.abs(w.astype(np.int64)).reshape(K, -1).sum(axis=1).argmax())
+    x_rand = si.int8_tensor(9202, (N, C, H, W))
+    x_adv = np.zeros((N, C, H, W), dtype=np.int8)
+    # the 3 x 3 patch around output (8, 8) of filter k0, chosen against the filter's signs: y[k0, 8, 8] = -128 * sum |w| + (#negative)
+    x_adv[0, :, 7:10, 7:10] = np.where(w[k0] > 0, -128, 127).astype(np.int8)
+    for x in (x_rand, x_adv):
+        y = layer.forward(torch.from_numpy(x).to("cuda:0")).cpu().numpy()
+        torch.cuda.synchronize()
+        assert np.array_equal(y, direct_conv2d(x, w, pad))
+    ref = direct_conv2d(x_adv, w, pad)
+    assert bound - 128 * 576 <= abs(int(ref[0, k0, 8, 8])) <= bound and abs(int(ref[0, k0, 8, 8])) > 0.3 * 251 * 241 * 239
+
+
+def test_vgg16_stack_with_weight_derived_bounds():
+    """The stack with every layer's moduli count taken from the bound of its own weights (three moduli where 128 * max_k sum |w|
+    fits their range: the two 64-channel layers besides the first one): every layer's activations are the CPU chain's."""
+    from paper_2007_12216_amd import select
+    from paper_2007_12216_amd.stack import ConvStack
+    print("stack weight bounds", flush=True)
+    batch, hw = 2, 32
+    layers = si.vgg16_stack(batch=batch, hw=hw)
+    weights = [si.int8_tensor(l["seed_w"], (l["K"], l["C"], l["r"], l["r"])) for l in layers]
+    for l, w in zip(layers, weights):
+        l["output_bound"] = select.output_bound_from_weights(w)
+        l["moduli"] = select.moduli_for_bound(l["output_bound"])
+    assert [len(l["moduli"]) for l in layers] == [3, 3, 3] + [4] * 10
+    x = si.int8_tensor(si.VGG16_SEED_X, (batch, 3, hw, hw))
+    stack = ConvStack(layers)
+    stack.set_weights(weights)
+    stack.forward(torch.from_numpy(x).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref_acts, _ = oracle_stack(layers, x, weights)
+    for li, (got, ref) in enumerate(zip(stack.act, ref_acts)):
+        assert np.array_equal(got.cpu().numpy(), ref), layers[li]["name"]
+
+
 def test_vgg16_stack_in_the_papers_setting():
     """Three 8-bit moduli on every layer with the range trusted (section 8 of the paper) instead of four from the worst-case
     bound: the outputs of the seeded data stay inside the dynamic range, so the chain is still the oracle's."""

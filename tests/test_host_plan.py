@@ -110,6 +110,31 @@ def test_range_rule():
     assert _code(C=512, K=512, H=28, W=28, m=14, moduli=(65521, 65519)) == 0
 
 
+def test_output_bound_from_the_layers_weights():
+    """rnswino_desc_t::output_bound: the range test against a bound the caller proves for the actual weights
+    (128 * max_k sum |w[k]|) instead of the worst case 2^14 r^2 C."""
+    import synth_inputs as si
+    from paper_2007_12216_amd import select
+    three = (251, 241, 239)                                                    # holds |y| <= 7 228 674
+    assert _code(C=64, K=64, H=32, W=32) == -5                                 # worst case 9 437 184
+    assert _code(C=64, K=64, H=32, W=32, output_bound=7228674) == 0
+    assert _code(C=64, K=64, H=32, W=32, output_bound=7228675) == -5
+    assert _code(C=64, K=64, H=32, W=32, output_bound=10 ** 12) == -5          # a bound above the worst case changes nothing
+    assert _code(C=16, output_bound=10 ** 12) == 0
+    # the bound of seeded uniform int8 weights is about half the worst case: 64 channels fit three moduli, 128 do not
+    w64 = si.int8_tensor(5012, (64, 64, 3, 3))
+    b64 = select.output_bound_from_weights(w64)
+    assert b64 == 128 * int(abs(w64.astype(int)).reshape(64, -1).sum(axis=1).max()) and 4_000_000 < b64 < 6_000_000
+    assert select.moduli_for_bound(b64) == three
+    w128 = si.int8_tensor(5032, (128, 128, 3, 3))
+    assert select.moduli_for_bound(select.output_bound_from_weights(w128)) == (251, 241, 239, 233)
+    # the conversion form follows the bound as well
+    plan = rn.rnswino_plan(1, 64, 64, 32, 32, 3, 8, 1, three, flags=HOST, output_bound=b64)
+    assert rn.rnswino_plan_describe(plan)["conversion"] == "unreduced-binary32"     # about a third of the product: binary32 has room
+    plan = rn.rnswino_plan(1, 64, 64, 32, 32, 3, 8, 1, three, flags=HOST, output_bound=7228674)
+    assert rn.rnswino_plan_describe(plan)["conversion"] == "unreduced-binary64"     # the edge of the range
+
+
 def test_sizes():
     plan = rn.rnswino_plan(1, 256, 256, 56, 56, 3, 8, 1, (251, 241, 239, 233), flags=HOST)
     assert (plan.Ho, plan.Wo, plan.T) == (56, 56, 49)
