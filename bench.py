@@ -303,7 +303,7 @@ def layer_name(cfg):
 
 
 def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tiles=False, number_systems=False, per_layer=False,
-                weight_bound=False):
+                weight_bound=False, gemm_64x16=False):
     """Workload 5: one step = one pass of the 13-layer VGG16 conv stack at batch 8 (conv, shift/clamp, pool chain)."""
     import numpy as np
     import torch
@@ -326,6 +326,9 @@ def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tile
         for l, w in zip(layers, weights):
             l["output_bound"] = select.output_bound_from_weights(w)
             l["moduli"] = select.moduli_for_bound(l["output_bound"])
+    if gemm_64x16:
+        for l in layers:
+            l["flags"] = l.get("flags", 0) | rn.FLAG_GEMM_BLOCK_64X16
     x_np = si.int8_tensor(si.VGG16_SEED_X, (8, 3, 224, 224))
     stack = ConvStack(layers, measured_tiles=measured_tiles, number_systems=number_systems)
     stack.set_weights(weights)
@@ -418,6 +421,7 @@ def bench_stack(steps, warmup, dev, with_cpu, trusted_range=False, measured_tile
             (", number system measured per layer" if number_systems else "") +
             (", RNS(251,241,239) with a trusted range on every layer" if trusted_range else "") +
             (", moduli count per layer from the bound of its own weights" if weight_bound else "") +
+            (", residue GEMM forced to 64 x 16 blocks (what a fused GEMM + inverse transform could hold on chip)" if gemm_64x16 else "") +
             ", shift/clamp + 2x2 max-pool fused into the inverse transform")
     return {"name": name, "ops": ops, "sec": sec, "rounds": rounds, "steps": steps, "warmup": warmup, "roofline": roofline,
             "bit_exact": bit_exact, "cpu": cpu, "tiles": [l["m"] for l in stack.cfg],
@@ -460,6 +464,9 @@ def main():
     ap.add_argument("--weight-bound", action="store_true",
                     help="workload 5 only: moduli count per layer from the output bound its own weights give (128 max_k sum |w|) "
                          "instead of the worst case 2^14 r^2 C")
+    ap.add_argument("--gemm-64x16", action="store_true",
+                    help="workload 5 only, measurement: residue GEMM on 64-row x 16-tile workgroup blocks, the largest block whose "
+                         "output a workgroup could keep in LDS for a fused inverse transform (prices that fusion)")
     ap.add_argument("--per-layer", action="store_true", help="workload 5 only: add a per-layer, per-kernel table of durations")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -482,7 +489,7 @@ def main():
 
     if args.workload == 5:
         r = bench_stack(K_steps, W_steps, dev, with_cpu, args.trusted_range, args.measured_tiles, args.number_systems, args.per_layer,
-                        args.weight_bound)
+                        args.weight_bound, args.gemm_64x16)
         out = dict(common, value=round(r["ops"] / r["sec"] / 1e12, 3), steps=r["steps"], warmup=r["warmup"],
                    ms_per_step=round(r["sec"] * 1e3, 5),
                    config={"workload": r["name"], "output_tiles": r["tiles"], "moduli": r["moduli"],

@@ -63,8 +63,13 @@ enum {
                                               output lies in [-(P-1)/2, (P-1)/2], P = prod m_i, as the paper
                                               does with a measured range (section 8); otherwise the output
                                               is the true result reduced to that interval (mod 2^32)       */
-  RNSWINO_FLAG_HOST_ONLY = 2u              /* build the host tables only (no GPU touched): such a plan can
+  RNSWINO_FLAG_HOST_ONLY = 2u,             /* build the host tables only (no GPU touched): such a plan can
                                               be queried but not executed                                   */
+  RNSWINO_FLAG_GEMM_BLOCK_64X16 = 4u       /* measurement only (8-bit moduli): run the residue GEMM on workgroup blocks
+                                              of 64 rows x 16 tiles -- the largest block whose GEMM output (n t^2
+                                              bytes per (k, tile) pair) one workgroup could keep in LDS if the
+                                              inverse transform were fused into the GEMM (section 6: the stages
+                                              compose per tile group).  Same result, slower; used to price that fusion */
 };
 
 typedef struct rnswino_plan_s rnswino_plan_t;   /* opaque, owned by the library */

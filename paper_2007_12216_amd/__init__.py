@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     rnswino_filter_bytes, rnswino_workspace_bytes, rnswino_output_dims, rnswino_plan_get_matrix, rnswino_plan_get_table,
     rnswino_plan_get_mrc_inverse, rnswino_plan_dynamic_range, rnswino_plan_describe, rnswino_kernel_variants, rnswino_debug_empty_launch, rnswino_debug_stage, rnswino_strerror,
     MATRIX_AT, MATRIX_G, MATRIX_BT, TABLE_INPUT, TABLE_INVERSE, STAGE_U, STAGE_V, STAGE_O,
-    FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY, EXPORTED_SYMBOLS,
+    FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY, FLAG_GEMM_BLOCK_64X16, EXPORTED_SYMBOLS,
 )

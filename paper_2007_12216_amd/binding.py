@@ -11,7 +11,7 @@ _LIB_PATH = os.path.join(_PKG, "librnswino.so")
 
 MATRIX_AT, MATRIX_G, MATRIX_BT = 0, 1, 2
 STAGE_U, STAGE_V, STAGE_O = 0, 1, 2
-FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY = 1, 2
+FLAG_ALLOW_UNCHECKED_RANGE, FLAG_HOST_ONLY, FLAG_GEMM_BLOCK_64X16 = 1, 2, 4
 
 EXPORTED_SYMBOLS = (
     "rnswino_plan", "rnswino_plan_destroy", "rnswino_output_dims", "rnswino_filter_bytes",

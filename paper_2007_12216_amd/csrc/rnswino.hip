@@ -192,12 +192,18 @@ void k2_grid(const Dims &d, int brf, int btf, K2Choice &c) {
   c.blocks = (unsigned)(8 * ((nxh + xgroup - 1) / xgroup * xgroup) * gy * gz);
 }
 
-K2Choice choose_k2(const Dims &d) {
+K2Choice choose_k2(const Dims &d, uint32_t flags) {
   K2Choice c;
   c.wide = d.wide != 0;
   c.lds = false; c.WM = c.WN = c.S = 0;
   const int ntb = d.Tp / 16, ncb = d.Cp / 64;
   c.NTB = ntb == 1 ? 1 : ntb == 2 ? 2 : 4;
+  if (!c.wide && (flags & RNSWINO_FLAG_GEMM_BLOCK_64X16)) {
+    // measurement only: the GEMM on the block a fused GEMM + inverse transform could hold on chip
+    c.lds = true; c.KS = 0; c.NTB = 1; c.WM = 4; c.WN = 1; c.RM = 1; c.S = 4;
+    k2_grid(d, 4, 1, c);
+    return c;
+  }
   if (!c.wide && d.Kp >= 128) {
     // LDS-tiled kernel where it measured faster than the register-direct one (VGG16 stack at batch 8, the 256-channel
     // layer at batch 1): 128 x 64 blocks for 33..64 tiles; 128 x 128 blocks for many tiles and a contraction of two or
@@ -281,7 +287,7 @@ K3Choice choose_k3(const Dims &d, const KParams &P, int n_cus, int epi) {
   X(1, 1, 2, false) X(2, 1, 2, false) X(4, 1, 2, false) X(1, 2, 2, false) X(2, 2, 2, false) X(4, 2, 2, false) \
   X(1, 4, 2, false) X(2, 4, 2, false) X(4, 4, 2, false) X(1, 4, 4, false) X(2, 4, 4, false) \
   X(1, 1, 2, true) X(2, 1, 2, true) X(4, 1, 2, true) X(1, 2, 2, true) X(2, 2, 2, true) X(1, 4, 2, true)
-#define RNSW_K2L_TABLE(X) X(2, 2, 4, 4, 3) X(4, 1, 2, 4, 4)
+#define RNSW_K2L_TABLE(X) X(2, 2, 4, 4, 3) X(4, 1, 2, 4, 4) X(4, 1, 1, 1, 4)
 #define RNSW_K3_NK(X, nres, wd, fs) X(nres, 1, wd, fs) X(nres, 2, wd, fs) X(nres, 3, wd, fs) X(nres, 4, wd, fs)
 #define RNSW_K3_TABLE(X) \
   RNSW_K3_NK(X, 1, true, false) RNSW_K3_NK(X, 2, true, false) RNSW_K3_NK(X, 3, true, false) RNSW_K3_NK(X, 4, true, false) \
@@ -307,8 +313,8 @@ bool launch_k1(const Dims &d, const KParams &P, const int8_t *x, int8_t *V, hipS
 }
 
 // ---- K2 ----
-bool launch_k2(const Dims &d, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm, bool dry = false) {
-  const K2Choice c = choose_k2(d);
+bool launch_k2(const Dims &d, uint32_t flags, const KParams &P, const int8_t *U, const int8_t *V, uint32_t *O, hipStream_t st, Timing tm, bool dry = false) {
+  const K2Choice c = choose_k2(d, flags);
   const dim3 grid(c.blocks);
   if (c.lds) {
 #define RNSW_X(wm_, wn_, rm, ntb, s_) \
@@ -389,7 +395,7 @@ int conv2d_impl(const rnswino_plan_t *plan, const int8_t *x_dev, const void *U_d
     t3.start = (hipEvent_t)events[4]; t3.stop = (hipEvent_t)events[5];
   }
   // (rnswino_plan() has checked that all three instantiations exist)
-  if (!launch_k1(d, P, x_dev, Vp, st, t1) || !launch_k2(d, P, (const int8_t *)U_dev, Vp, Op, st, t2) ||
+  if (!launch_k1(d, P, x_dev, Vp, st, t1) || !launch_k2(d, plan->desc.flags, P, (const int8_t *)U_dev, Vp, Op, st, t2) ||
       !launch_k3(d, P, plan->n_cus, Op, y_dev, st, t3))
     return RNSWINO_E_UNSUPPORTED;
   return launch_status();
@@ -457,7 +463,7 @@ int rnswino_plan(rnswino_plan_t **out, const rnswino_desc_t *desc) {
   {
     // every kernel the layer would launch, in each output mode, must be an instantiation that exists
     KParams P = *(const KParams *)pl->kparams;
-    bool ok = launch_k1(d, P, nullptr, nullptr, nullptr, Timing(), true) && launch_k2(d, P, nullptr, nullptr, nullptr, nullptr, Timing(), true);
+    bool ok = launch_k1(d, P, nullptr, nullptr, nullptr, Timing(), true) && launch_k2(d, pl->desc.flags, P, nullptr, nullptr, nullptr, nullptr, Timing(), true);
     for (int epi = 0; epi < 3 && ok; ++epi) {
       P.epi = epi;
       ok = launch_k3(d, P, pl->n_cus, nullptr, nullptr, nullptr, Timing(), true);
@@ -553,7 +559,7 @@ int64_t rnswino_plan_describe(const rnswino_plan_t *plan, int32_t output_mode, c
   const Dims &d = plan->dims;
   const KParams &P = *(const KParams *)plan->kparams;
   const K1Choice c1 = choose_k1(d);
-  const K2Choice c2 = choose_k2(d);
+  const K2Choice c2 = choose_k2(d, plan->desc.flags);
   const K3Choice c3 = choose_k3(d, P, plan->n_cus, output_mode);
   auto tf = [](bool b) { return b ? "true" : "false"; };
   char buf[1024];

@@ -52,6 +52,7 @@ def _candidates():
     for C, K, hw in itertools.product((60, 128, 256), (24, 130, 200), (40, 64)):
         add(1, C, K, hw, hw, 3, 6, 1, PRIMES8[:4])
     add(1, 40, 136, 36, 36, 3, 7, 1, PRIMES8[:3])            # t = 9: a last point group with one point, LDS-tiled
+    add(1, 70, 40, 40, 40, 3, 8, 1, PRIMES8[:4], rn.FLAG_GEMM_BLOCK_64X16)       # the measurement form of the LDS-tiled GEMM
     # (c) 64-row GEMM blocks: K >= 256, two or more channel blocks (even and odd), enough work items
     for C in (128, 192):
         add(3, C, 256, 64, 64, 3, 8, 1, PRIMES8[:4])
