@@ -32,9 +32,11 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // One 16-byte-per-lane load from global memory straight into LDS: lane l's 16 bytes from base + lane_off land at
-// lds_addr + 16 l (lds_addr: wave-uniform byte address within LDS, passed in M0).
+// lds_addr + 16 l (lds_addr: wave-uniform byte address within LDS, passed in M0).  The s_nop is the wait state the
+// instruction set asks for between a scalar write of M0 and an LDS-direct load that reads it (the compiler inserts it for
+// its own code, not inside inline assembly).
 __device__ __forceinline__ void load_to_lds16(const void *base, uint32_t lane_off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 
 template <int WM, int WN, int RM, int NT, int S>
