@@ -688,3 +688,16 @@ def test_requant_pool_at_the_ends_of_the_shift_range():
         rn.rnswino_requant_pool(yd, a, 1, 2, 6, shift, False, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         assert np.array_equal(a.cpu().numpy(), requant_shift_clamp(y, shift)), shift
+
+
+def test_empty_launch_for_floor_measurements():
+    """rnswino_debug_empty_launch: any grid, with and without events; bad grids are refused without a launch."""
+    print("empty launch", flush=True)
+    st = torch.cuda.current_stream().cuda_stream
+    for grid in ((1, 1), (200, 4), (20000, 1)):
+        rn.rnswino_debug_empty_launch(grid[0], grid[1], st)
+    torch.cuda.synchronize()
+    for grid in ((0, 1), (1, 0), (1, 70000)):
+        with pytest.raises(rn.RnsWinoError) as e:
+            rn.rnswino_debug_empty_launch(grid[0], grid[1], st)
+        assert e.value.code == -1

@@ -109,3 +109,12 @@ def test_16_bit_moduli_refuse_contractions_of_1024_steps():
         return 0
     assert code(65472) == 0 and code(65473) == -2
     assert code(131071) == -2
+
+
+def test_measurement_flag_selects_the_64_by_16_gemm_blocks():
+    plain = rn.rnswino_plan(8, 64, 64, 56, 56, 3, 8, 1, (251, 241, 239, 233), flags=HOST)
+    forced = rn.rnswino_plan(8, 64, 64, 56, 56, 3, 8, 1, (251, 241, 239, 233), flags=HOST | rn.FLAG_GEMM_BLOCK_64X16)
+    assert rn.rnswino_plan_describe(plan=plain)["kernels"][1] == "k2_residue_gemm<1, 4, 2, false>"
+    assert rn.rnswino_plan_describe(plan=forced)["kernels"][1] == "k2_residue_gemm_lds<4, 1, 1, 1, 4>"
+    wide = rn.rnswino_plan(1, 64, 64, 28, 28, 3, 14, 1, (65521, 65519), flags=HOST | rn.FLAG_GEMM_BLOCK_64X16)
+    assert rn.rnswino_plan_describe(plan=wide)["kernels"][1].startswith("k2_residue_gemm<")      # 8-bit moduli only
