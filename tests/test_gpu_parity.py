@@ -554,12 +554,14 @@ def test_two_streams_with_their_own_workspaces():
         assert np.array_equal(ys[j].cpu().numpy(), direct_conv2d(xs[j], w, pad))
 
 
-def test_captured_graph_replays_match_the_eager_result():
+@pytest.mark.parametrize("K,hw", [(32, 24), (128, 48)])
+def test_captured_graph_replays_match_the_eager_result(K, hw):
     """rnswino_conv2d neither allocates nor synchronises, so its three launches can be captured into a HIP graph; every
-    replay (with eager work and synchronisations of the program's own in between) must give the eager result."""
-    print("graph capture", flush=True)
+    replay (with eager work and synchronisations of the program's own in between) must give the eager result.  The second
+    shape runs the LDS-tiled GEMM (its loads are issued from inline assembly: nothing a capture could trip over)."""
+    print("graph capture", K, hw, flush=True)
     from paper_2007_12216_amd.layer import ConvLayer
-    N, C, K, H, W, r, m, pad, moduli = 1, 64, 32, 24, 24, 3, 8, 1, (251, 241, 239, 233)
+    N, C, H, W, r, m, pad, moduli = 1, 64, hw, hw, 3, 8, 1, (251, 241, 239, 233)
     w = si.int8_tensor(91, (K, C, r, r))
     layer = ConvLayer(N, C, K, H, W, r, m, pad, moduli)
     layer.set_weights(w)
