@@ -328,11 +328,12 @@ __global__ __launch_bounds__(256) void k3_inverse_crt(KParams P, const uint32_t 
 }
 
 // Streaming variant for layers with many tiles (8-bit moduli, table of all residues <= 64 KiB): the table is staged
-// once per block in LDS, and every wave walks over units = (k, block of 16 tiles) with a grid stride, loading the O
-// operand of its next unit while the current one is multiplied and converted.  Per unit a wave issues only its own
-// O loads (no table reads from global memory, no copies of O in other waves); the table fragments come from LDS.
-// Grid: min(ceil(units / 4), three blocks per CU) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
-constexpr int K3_STREAM_BLOCKS = 768;   // three resident blocks per CU (register budget) on 256 CUs
+// once per block in LDS, and every wave walks over units = (k, block of 16 tiles) with a grid stride.  Per unit a wave
+// issues only its own O loads (no table reads from global memory, no copies of O in other waves); the table fragments
+// come from LDS.  A unit's loads are hidden by the other waves of the SIMD (four resident blocks per CU; a second
+// register set that prefetched the next unit's operand cost a block of occupancy and measured 3-10 % slower).
+// Grid: min(ceil(units / 4), four blocks per CU) blocks of 256 threads; dynamic LDS = n * RB3 * KS3 KiB.
+constexpr int K3_STREAM_BLOCKS = 1024;  // four resident blocks per CU (register budget) on 256 CUs
 
 // M8: 8 x 8 output tiles (four row blocks), the usual case: where a lane's outputs go inside the tile is computed once
 // per kernel instead of once per row block, and the table fragments of a row block sit at immediate LDS offsets.
@@ -374,8 +375,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
     }
   };
 
-  // One unit with its O operand in `o`, while the operand of the wave's next unit travels into `onext`; the loop
-  // alternates the two register sets (a copy would wait for every memory operation issued before it).
+  // One unit with its O operand in `o`.
   const int a0 = FAST ? P.acc0 : 0;                 // 2^22 for the fast conversion
   const v4i acc_start = (v4i){a0, a0, a0, a0};
   // 8 x 8 tiles: outputs 16 rb + 4 g .. + 3 are row u = 2 rb + (g >> 1), columns v = 4 (g & 1) .. + 3 of the tile; in the
@@ -383,8 +383,7 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
   const int m8_u0 = g >> 1, m8_v = 4 * (g & 1);
   const uint32_t m8_step = P.epi == 2 ? (uint32_t)(P.Wo >> 1) : (uint32_t)(2 * P.Wo);
   const uint32_t m8_off0 = P.epi == 2 ? (uint32_t)(m8_v >> 1) : (uint32_t)(m8_u0 * P.Wo + m8_v);
-  auto do_unit = [&](int u, v4i (&o)[NRES][KS3], v4i (&onext)[NRES][KS3]) {
-    if (u + nwaves < nunits) load_o(u + nwaves, onext);
+  auto do_unit = [&](int u, v4i (&o)[NRES][KS3]) {
     const int kg = u / ntb, taug = (u - kg * ntb) * 16 + (lane & 15);
     const int k = kg / P.TL, tau = taug < P.Tg ? (kg % P.TL) * P.Tg + taug : P.T;   // packed layers: see plan.hpp
     const TilePos tp = tile_position(P, k, tau);
@@ -432,12 +431,10 @@ __global__ __launch_bounds__(256) void k3_inverse_crt_stream(KParams P, const ui
       k3_convert_and_store<NRES, FAST>(P, w, rb, g, tp, y);
     }
   };
-  v4i oa[NRES][KS3], ob[NRES][KS3];
-  load_o(unit, oa);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the loop is entered with nothing pending
-  for (; unit < nunits; unit += 2 * nwaves) {
-    do_unit(unit, oa, ob);
-    if (unit + nwaves < nunits) do_unit(unit + nwaves, ob, oa);
+  v4i oa[NRES][KS3];
+  for (; unit < nunits; unit += nwaves) {
+    load_o(unit, oa);
+    do_unit(unit, oa);
   }
 }
 

@@ -243,7 +243,7 @@ K2Choice choose_k2(const Dims &d, uint32_t flags) {
 }
 
 // stream: the streaming variant (8-bit moduli, table of all residues at most 64 KiB, n * KS3 <= 8: O operand in
-// registers twice) for layers with a unit or more per wave of the full grid (measured on the VGG16 stack);
+// registers) for layers with 3072 and more units (measured on the VGG16 stack);
 // fast: conversion out of the RNS from unreduced accumulators; m8: the 8 x 8 store path of the streaming variant
 // (int32 output: only with rows that keep four outputs 16-byte aligned; int8 output: only with an even row length).
 struct K3Choice { bool stream, wide, fast, m8; int NRES, KS3; unsigned gx, gy; size_t lds; };
@@ -255,12 +255,12 @@ K3Choice choose_k3(const Dims &d, const KParams &P, int n_cus, int epi) {
   c.KS3 = d.KS3 < 4 ? d.KS3 : 4;
   c.fast = !c.wide && P.fastcrt != 0;
   c.stream = !c.wide && d.n * d.KS3 <= 8 && d.n <= 4 && d.KS3 <= 2 && (size_t)d.n * d.RB3 * d.KS3 * 1024 <= 65536 &&
-             (long long)d.Kg * (d.Tp / 16) >= 4LL * K3_STREAM_BLOCKS;
+             (long long)d.Kg * (d.Tp / 16) >= 3072;
   c.m8 = false;
   c.lds = 0;
   if (c.stream) {
     const long long blocks = ((long long)d.Kg * (d.Tp / 16) + 3) / 4;
-    const long long max_blocks = n_cus > 0 ? 3LL * n_cus : K3_STREAM_BLOCKS;
+    const long long max_blocks = n_cus > 0 ? 4LL * n_cus : K3_STREAM_BLOCKS;
     c.gx = (unsigned)(blocks < max_blocks ? blocks : max_blocks);
     c.gy = 1;
     c.lds = (size_t)d.n * d.RB3 * d.KS3 * 1024;
